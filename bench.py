@@ -1,0 +1,168 @@
+#!/usr/bin/env python3
+"""Throughput of the whole hot path on one MI355X.
+
+Workload (the largest single-GPU configuration): W = 256 workers x B = 256 images.  One step =
+the server is down for 4 worker rounds (4 x worker_grads_batched over 65,536 images on the last
+published snapshot -> 1024 buffered gradients, 3.3 GB), then recovers: ps_drain_buffered applies
+the backlog (odd steps as one summed update, even steps as 1024 successive updates) and the new
+weights are published with ps_snapshot_weights.  Inputs are synthetic, seeded, and resident in HBM
+before the timed region.
+
+Prints ONE JSON line: whole-step images/s, plus the roofline of the dominant kernel (timed live
+with HIP events on the library's stream), the drain's HBM roofline, a per-kernel table, and the CPU
+oracle timed on a bounded sample as a baseline.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+W, B, ROUNDS = 256, 256, 4
+LR = 0.005
+P = 813258
+PEAK_MFMA_F32_TFLOPS = 157.3
+PEAK_HBM_GBPS = 8000.0
+FLOP_PER_IMAGE = 10718208
+
+# algorithmic FLOP per image of each worker kernel (2 x multiply-accumulates of the layer it computes)
+KERNEL_FLOP_PER_IMAGE = {
+    "conv1_fwd_kernel": 225792, "conv2_fwd_kernel": 1806336, "gemm_f32_mfma<true, true, Fc1FwdEpi>": 1605632,
+    "fc2_kernel": 20480, "fc2_grad_kernel": 10240, "gemm_f32_mfma<false, false, Fc1DwEpi>": 1605632,
+    "gemm_f32_mfma<false, true, Fc1DxEpi>": 1605632, "conv2_dw_kernel": 1806336, "conv2_dx_kernel": 1806336,
+    "conv1_dw_kernel": 225792, "conv_grad_reduce_kernel": 0,
+}
+APPLY_KERNELS = ("apply_kernel<0>", "apply_kernel<1>")
+
+
+def cpu_baseline():
+    """The oracle as it stands, on the host cores, on a bounded sample of the same workload."""
+    import numpy as np
+    from oracle import oracle as orc
+    from paper_2406_05546_amd import synth
+    threads = min(16, len(os.sched_getaffinity(0)))
+    n = threads                                            # one 256-image worker per thread
+    mbs = [synth.minibatch_id(w, 0) for w in range(n)]
+    x, y = synth.minibatches(1, mbs, B)
+    theta = synth.he_uniform_theta(1).astype(np.float64)
+    keep = np.stack([orc.dropout_keep(7, m, B, 512, 0.25) for m in mbs])
+    t0 = time.perf_counter()
+    _, _, used = orc.worker_grads(orc.Dims(), theta[None], [0] * n, x, y, keep, 0.25, n_threads=threads)
+    dt = time.perf_counter() - t0
+    # drain: 64 of the 1024 buffered rows, full width, sequential rule
+    rows = synth.gradient_rows(2, 0, 64, P)
+    t1 = time.perf_counter()
+    orc.drain(theta, list(rows), LR, orc.DRAIN_SEQ)
+    dd = time.perf_counter() - t1
+    return {"value": n * B / dt, "unit": "images/s", "cores": used, "kind": "oracle",
+            "sample": f"{n} workers x {B} images fwd+bwd in {dt:.1f} s on {used} threads; drain of 64 of 1024 rows "
+                      f"x {P} floats in {dd:.2f} s on 1 thread",
+            "drain_GBps": (64 * P * 4 + 2 * P * 4) / dd / 1e9}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=8)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (workers are a batch dimension); use --gpus 1")
+
+    import numpy as np
+    import torch
+    from paper_2406_05546_amd import binding as ps
+    from paper_2406_05546_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    dev = "cuda:0"
+    ctx = ps.ps_init(ps.make_config(W, B, 1, W * ROUNDS, 0xD0D0, 0.25), dev)
+    ps.ps_set_weights(ctx, synth.he_uniform_theta(1))
+    xs, ys = [], []
+    for r in range(ROUNDS):
+        x, y = synth.minibatches(1, [synth.minibatch_id(w, r) for w in range(W)], B)
+        xs.append(torch.from_numpy(x).to(dev))
+        ys.append(torch.from_numpy(y).to(dev))
+    loss = torch.zeros(W, device=dev)
+    workers, slots = list(range(W)), [0] * W
+
+    def step(i):
+        for r in range(ROUNDS):
+            mbs = [synth.minibatch_id(w, i * ROUNDS + r) for w in workers]
+            ps.worker_grads_batched(ctx, workers, slots, mbs, xs[r], ys[r], loss)
+        k = ps.ps_drain_buffered(ctx, ps.DRAIN_SUM if i % 2 else ps.DRAIN_SEQ, LR)
+        assert k == W * ROUNDS
+        ps.ps_snapshot_weights(ctx, 0)
+
+    for i in range(args.warmup):
+        step(i)
+    ps.ps_sync(ctx)
+    torch.cuda.synchronize()
+    ps.ps_profile_enable(ctx, True)
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    ps.ps_sync(ctx)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = ps.ps_profile_read(ctx)
+    ps.ps_profile_enable(ctx, False)
+    final_loss = float(loss.mean().item())
+    assert np.isfinite(ps.ps_get_weights(ctx)).all() and np.isfinite(final_loss)
+    ps.ps_destroy(ctx)
+
+    images_per_step = W * B * ROUNDS
+    n_launch_images = W * B
+    kernels = []
+    for name, (ms, n) in prof.items():
+        if n == 0:
+            continue
+        avg = ms / n
+        if name in APPLY_KERNELS:
+            algo = W * ROUNDS * P * 4 + 2 * P * 4
+            ach = algo / (avg * 1e-3) / 1e9
+            kernels.append({"kernel": name, "launches": n, "avg_ms": avg, "bound": "hbm", "achieved": ach,
+                            "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBPS, "total_ms": ms})
+        else:
+            flop = KERNEL_FLOP_PER_IMAGE[name] * n_launch_images
+            ach = flop / (avg * 1e-3) / 1e12
+            kernels.append({"kernel": name, "launches": n, "avg_ms": avg, "bound": "mfma", "achieved": ach,
+                            "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_MFMA_F32_TFLOPS,
+                            "total_ms": ms})
+    kernels.sort(key=lambda k: -k["total_ms"])
+    dom = kernels[0]
+    roofline = {k: dom[k] for k in ("bound", "achieved", "peak", "unit", "frac")}
+    roofline.update({"kernel": dom["kernel"], "avg_ms": dom["avg_ms"], "traffic": None})
+    drains = [k for k in kernels if k["kernel"] in APPLY_KERNELS]
+    worker_ms = sum(k["total_ms"] for k in kernels if k["kernel"] not in APPLY_KERNELS)
+    worker_tflops = FLOP_PER_IMAGE * images_per_step * args.steps / (worker_ms * 1e-3) / 1e12 if worker_ms else 0.0
+
+    out = {
+        "metric": "worker gradient images/sec (fwd+bwd) at 1 GPU, whole step incl. buffered-grad drain",
+        "value": images_per_step * args.steps / dt, "unit": "images/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"outage_w256_b256: {ROUNDS} rounds x W={W} workers x B={B} images on one snapshot "
+                               f"-> {W * ROUNDS} buffered gradients (3.33 GB) -> drain (SUM/SEQ alternating) -> publish",
+                   "images_per_step": images_per_step, "lr": LR, "dropout_p": 0.25},
+        "roofline": roofline,
+        "worker_kernels_sum": {"achieved": worker_tflops, "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s",
+                               "frac": worker_tflops / PEAK_MFMA_F32_TFLOPS,
+                               "images_per_s_kernel_time": images_per_step * args.steps / (worker_ms * 1e-3)},
+        "drain": [{k: d[k] for k in ("kernel", "avg_ms", "achieved", "peak", "unit", "frac", "launches")}
+                  for d in drains],
+        "kernels": [{k: v for k, v in kk.items() if k != "total_ms"} for kk in kernels],
+        "final_mean_loss": final_loss,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,183 @@
+/*
+ * ps_hotpath.h -- C ABI of the parameter-server hot path of "Training Through
+ * Failure: Effects of Data Consistency in Parallel Machine Learning Training"
+ * (arxiv 2406.05546) for one AMD MI355X (gfx950).
+ *
+ * W simulated workers are a batch dimension on one GPU.  Each worker runs the
+ * forward/backward pass of the paper's CNN (model endnote: conv 16, ReLU, max
+ * pool, conv 32, ReLU, max pool, FC 512, ReLU, dropout 25 %, FC 10) on its own
+ * minibatch against the weight snapshot it last pulled, which may be stale.
+ * The server applies the resulting gradients by the paper's three rules:
+ *   sync      (Section 2.1, Section 3.1)  wait for all, one update with all
+ *   async     (Section 2.1, Section 3.1)  one update per arriving gradient
+ *   stateless (Section 2.3, Section 3.3)  gradients are appended to a pending
+ *             list; a server step applies ALL pending ones and publishes; while
+ *             the server is down the list only grows and is applied on recovery
+ * "Server down" is not library state: the caller simply stops calling apply.
+ *
+ * Conventions
+ *   - Every function returns a ps_status and never throws across the ABI.
+ *     ps_last_error() gives a message for the last failing call on a context.
+ *   - Pointers named *_dev are DEVICE pointers borrowed for the duration of the
+ *     enqueued work; pointers named *_host are HOST pointers owned by the caller.
+ *   - All GPU work is enqueued on the HIP stream given to ps_init and is
+ *     asynchronous; the ps_get_*, ps_debug_* and ps_sync calls wait for it.
+ *   - The library allocates no device memory: the caller hands ps_init one
+ *     device workspace of ps_workspace_bytes() bytes, which the context carves
+ *     into weights, snapshot ring, gradient queue and activations, and which
+ *     must outlive the context.
+ *   - Not thread-safe per context.
+ *
+ * Flat parameter vector, P = 813,258 floats, offsets in floats:
+ *   conv1.W[16][1][3][3] @0, conv1.b[16] @144, conv2.W[32][16][3][3] @160,
+ *   conv2.b[32] @4768, fc1.W[512][1568] @4800 (input index = c*49 + y*7 + x),
+ *   fc1.b[512] @807616, fc2.W[10][512] @808128, fc2.b[10] @813248.
+ * Readings where the paper is silent (kernel 3x3 pad 1, pool 2x2, softmax
+ * cross-entropy, inverted dropout, SUM aggregation, plain SGD) are listed in
+ * the design notes.
+ */
+#ifndef PS_HOTPATH_H
+#define PS_HOTPATH_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PS_API __attribute__((visibility("default")))
+
+#define PS_PARAM_COUNT 813258
+#define PS_IMAGE_PIXELS 784
+#define PS_N_CLASSES 10
+#define PS_FC1_UNITS 512
+#define PS_POOL1_SIZE 3136 /* 16 x 14 x 14 */
+#define PS_POOL2_SIZE 1568 /* 32 x 7 x 7   */
+
+typedef struct ps_ctx ps_ctx;
+
+typedef enum {
+    PS_OK = 0,
+    PS_EINVAL = 1,  /* bad argument: null pointer, index or size out of range        */
+    PS_ENOMEM = 2,  /* workspace too small                                           */
+    PS_ESTATE = 3,  /* queue entry not pending (already applied or never written)    */
+    PS_EFULL = 4,   /* gradient queue has too few free entries; nothing was appended */
+    PS_EDEVICE = 5  /* a HIP call failed                                             */
+} ps_status;
+
+typedef struct {
+    int32_t max_workers;    /* largest n accepted by one worker_grads_batched call, >= 1 */
+    int32_t batch;          /* B, images per worker minibatch, >= 1                      */
+    int32_t n_versions;     /* V, snapshot ring slots, >= 1                              */
+    int32_t queue_capacity; /* most gradients pending at once, >= 1                      */
+    uint64_t seed;          /* key of the dropout generator                              */
+    float dropout_p;        /* in [0, 1); the paper's model uses 0.25                    */
+} ps_config;
+
+typedef enum { PS_DRAIN_SUM = 0, PS_DRAIN_SEQ = 1 } ps_drain_mode;
+
+/* Device bytes ps_init needs for this configuration. */
+PS_API ps_status ps_workspace_bytes(const ps_config* cfg, uint64_t* bytes_out);
+
+/* Creates a context over the caller's device workspace (256-byte aligned,
+ * >= ps_workspace_bytes()) on `hip_stream` (a hipStream_t, or NULL for the
+ * default stream) of the current device.  Weights, ring and queue start zeroed,
+ * version 0, queue empty.  On failure *out is NULL. */
+PS_API ps_status ps_init(ps_ctx** out, const ps_config* cfg, void* workspace_dev, uint64_t workspace_bytes,
+                  void* hip_stream);
+
+/* Waits for enqueued work, releases host resources.  The workspace stays the caller's. */
+PS_API ps_status ps_destroy(ps_ctx* ctx);
+
+/* Blocks until everything enqueued on the context's stream has finished. */
+PS_API ps_status ps_sync(ps_ctx* ctx);
+
+/* theta := theta_host[P]; every ring slot := theta; version := 0.  Queue must be empty (else PS_ESTATE). */
+PS_API ps_status ps_set_weights(ps_ctx* ctx, const float* theta_host);
+
+/* Copies P floats to the host: the server's current weights (slot = -1) or ring slot `slot`. */
+PS_API ps_status ps_get_weights(ps_ctx* ctx, int32_t slot, float* theta_host);
+
+/* A worker pulls the weights (Section 2.1: workers pull a snapshot; Section 3.3 worker step:
+ * read the stored weights): ring[slot] := theta.  *version_out (may be NULL) receives the
+ * number of weight updates applied so far, which is the snapshot's version. */
+PS_API ps_status ps_snapshot_weights(ps_ctx* ctx, int32_t slot, uint64_t* version_out);
+
+/* Worker step, batched (Section 3.3 worker pseudo-code; Section 2.3 for the outage case):
+ * for i in [0, n): worker worker_id_host[i] computes the gradient of its mean minibatch loss
+ * (softmax cross-entropy) at the snapshot in ring slot version_slot_host[i], on images
+ * x_dev[i][B][784] (fp32) with labels y_dev[i][B] (int32 in [0,10)), and appends it to the
+ * pending queue.  Entries are appended in array order, which is their arrival order.
+ * minibatch_id_host[i] is the minibatch's logical 64-bit id; with the seed it keys the
+ * dropout mask: unit u of sample s is dropped iff word u%4 of
+ * Philox4x32-10(counter {id_lo, id_hi, s, u/4}, key {seed_lo, seed_hi}) < floor(p * 2^32);
+ * kept units are scaled by 1/(1-p).
+ * queue_index_host[i] receives the queue entry holding gradient i.  loss_dev (device, [n], may
+ * be NULL) receives each worker's mean loss.  n = 0 is a no-op.  n > max_workers, a slot outside
+ * the ring or a null array give PS_EINVAL; fewer than n free entries give PS_EFULL. */
+PS_API ps_status worker_grads_batched(ps_ctx* ctx, int32_t n, const int32_t* worker_id_host,
+                               const int32_t* version_slot_host, const uint64_t* minibatch_id_host,
+                               const float* x_dev, const int32_t* y_dev, int32_t* queue_index_host,
+                               float* loss_dev);
+
+/* Appends a gradient produced elsewhere (the worker-side append of the stateless pseudo-code,
+ * Section 3.3): grad_host[P] is copied into a free queue entry with the given metadata. */
+PS_API ps_status ps_queue_push_host(ps_ctx* ctx, const float* grad_host, int32_t worker_id, uint64_t version,
+                             uint64_t minibatch_id, int32_t* queue_index_host);
+
+/* Synchronous rule (Section 2.1, Section 3.1): one update with all n listed pending gradients,
+ * theta := theta - lr * (g_0 + ... + g_{n-1}) summed in list order; the entries are then freed.
+ * Version += 1.  n = 0 is a no-op.  A listed entry that is not pending, or listed twice, gives
+ * PS_ESTATE and nothing is applied. */
+PS_API ps_status ps_apply_sync(ps_ctx* ctx, const int32_t* queue_index_host, int32_t n, float lr);
+
+/* Asynchronous rule (Section 2.1, Section 3.1): theta := theta - lr * g for one arrived
+ * gradient; the entry is freed.  Version += 1. */
+PS_API ps_status ps_apply_async(ps_ctx* ctx, int32_t queue_index, float lr);
+
+/* Stateless server step / recovery (Section 2.3; Section 3.3 server pseudo-code): applies every
+ * pending gradient in arrival order, either as one update with their sum (PS_DRAIN_SUM,
+ * version += 1) or as one update per gradient (PS_DRAIN_SEQ, version += K), then empties the
+ * queue.  *n_applied_host (may be NULL) receives K; K = 0 changes nothing. */
+PS_API ps_status ps_drain_buffered(ps_ctx* ctx, int32_t mode, float lr, int32_t* n_applied_host);
+
+/* Copies pending gradient `queue_index` (P floats) to the host. */
+PS_API ps_status ps_get_grad(ps_ctx* ctx, int32_t queue_index, float* grad_host);
+
+/* Pending entries in arrival order.  *n_host receives their number K; each array (may be NULL)
+ * must hold `capacity` items and receives min(K, capacity): arrival sequence number, worker id,
+ * version of the snapshot used, minibatch id, queue entry index. */
+PS_API ps_status ps_queue_meta(ps_ctx* ctx, int32_t capacity, int32_t* n_host, uint64_t* seq_host,
+                        int32_t* worker_host, uint64_t* version_host, uint64_t* minibatch_host,
+                        int32_t* queue_index_host);
+
+/* Number of weight updates applied so far. */
+PS_API ps_status ps_version(ps_ctx* ctx, uint64_t* version_host);
+
+/* Decisions taken for worker i of the most recent worker_grads_batched call (any pointer may be
+ * NULL): pool1_host[B][3136] and pool2_host[B][1568] hold, per pooled output, bits 0-1 = winner
+ * of the 2x2 window (dy*2+dx, first maximum wins) and bit 2 = 1 iff the winner's pre-activation
+ * is > 0; keep_host[B][512] the dropout keep mask (1 = kept); hdrop_host[B][512] the fc1
+ * activation after ReLU and dropout; z_host[B][10] the logits; pred_host[B] the arg-max class
+ * (lowest index on ties). */
+PS_API ps_status ps_debug_last_batch(ps_ctx* ctx, int32_t i, uint8_t* pool1_host, uint8_t* pool2_host,
+                              uint8_t* keep_host, float* hdrop_host, float* z_host, int32_t* pred_host);
+
+/* Per-kernel timing (instrumentation, not part of the method).  While enabled, every kernel launch
+ * of this context is bracketed by two HIP events on the context's stream.  ps_profile_enable waits
+ * for the stream, clears the totals and switches timing on (enable != 0) or off.  ps_profile_read
+ * waits for the stream and reports the summed duration and number of launches of kernel
+ * `kernel_id` in [0, ps_profile_kernel_count()); ps_profile_kernel_name gives the kernel's function
+ * name as a profiler prints it ("" for an unknown id). */
+PS_API ps_status ps_profile_enable(ps_ctx* ctx, int32_t enable);
+PS_API ps_status ps_profile_read(ps_ctx* ctx, int32_t kernel_id, double* total_ms_host, int64_t* launches_host);
+PS_API int32_t ps_profile_kernel_count(void);
+PS_API const char* ps_profile_kernel_name(int32_t kernel_id);
+
+/* Message of the last failing call on this context ("" if none); valid until the next call. */
+PS_API const char* ps_last_error(const ps_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PS_HOTPATH_H */

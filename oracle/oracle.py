@@ -174,7 +174,7 @@ def worker_grads(dims: Dims, thetas: np.ndarray, theta_of: Sequence[int], x: np.
     grads = np.empty((n, dims.P), dtype=np.float64)
     losses = np.empty(n, dtype=np.float64)
     if n_threads <= 0:
-        n_threads = len(os.sched_getaffinity(0))
+        n_threads = min(16, len(os.sched_getaffinity(0)))
     used = _load().oracle_worker_grads(ctypes.byref(dims._c()), n, _ptr(thetas), _ptr(theta_of), _ptr(x),
                                        _ptr(y), B, _ptr(keep), ctypes.c_double(1.0 / (1.0 - p)), _ptr(grads),
                                        _ptr(losses), n_threads)

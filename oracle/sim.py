@@ -1,0 +1,47 @@
+"""Replays an event list (see the harness's scenario description) on the CPU oracle.
+TEST INFRASTRUCTURE ONLY; never imported by the product path."""
+from __future__ import annotations
+
+from typing import Callable, Dict, List, Optional
+
+import numpy as np
+
+from . import oracle as orc
+
+
+class OracleReplay:
+    def __init__(self, scenario, data_seed: int, dropout_seed: int, theta0: np.ndarray, minibatches: Callable,
+                 dropout_p: float = 0.25, dims: orc.Dims = orc.Dims(), n_threads: int = 0):
+        """`minibatches(data_seed, mb_ids, batch)` is the harness's input generator."""
+        self.sc = scenario
+        self.data_seed = data_seed
+        self.minibatches = minibatches
+        self.server = orc.OracleServer(dims, seed=dropout_seed, dropout_p=dropout_p, n_slots=scenario.n_slots,
+                                       theta=theta0, n_threads=n_threads)
+        self.meta_log: List[tuple] = []
+        self.grads: Dict[int, np.ndarray] = {}
+        self.losses: Dict[int, float] = {}
+
+    def run(self, keep_grads: Optional[Callable[[int], bool]] = None) -> np.ndarray:
+        sv = self.server
+        for ev in self.sc.events:
+            kind = ev[0]
+            if kind == "grads":
+                _, workers, slots, mbs = ev
+                x, y = self.minibatches(self.data_seed, mbs, self.sc.batch)
+                for e in sv.worker_grads_batched(workers, slots, mbs, x, y):
+                    self.meta_log.append((e.seq, e.worker, e.version, e.mb_id))
+                    self.losses[e.seq] = e.loss
+                    if keep_grads is None or keep_grads(e.seq):
+                        self.grads[e.seq] = e.grad
+            elif kind == "sync":
+                sv.apply_sync(ev[1], ev[2])
+            elif kind == "async":
+                sv.apply_async(ev[1], ev[2])
+            elif kind == "drain":
+                sv.drain_buffered(ev[1], ev[2])
+            elif kind == "snapshot":
+                sv.snapshot_weights(ev[1])
+            else:
+                raise ValueError(kind)
+        return sv.theta

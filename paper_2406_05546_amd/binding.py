@@ -1,0 +1,263 @@
+"""ctypes binding of libps_hotpath.so: same names as include/ps_hotpath.h, argument marshalling
+only.  torch supplies device memory (the workspace, inputs) and the stream; every step of the
+path runs in the library's HIP kernels.  There is no fallback: if the library is missing or a
+call fails, an exception is raised."""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+P = 813258
+IMAGE_PIXELS = 784
+N_CLASSES = 10
+FC1_UNITS = 512
+POOL1_SIZE = 3136
+POOL2_SIZE = 1568
+DRAIN_SUM = 0
+DRAIN_SEQ = 1
+
+PS_OK, PS_EINVAL, PS_ENOMEM, PS_ESTATE, PS_EFULL, PS_EDEVICE = range(6)
+_STATUS = {0: "PS_OK", 1: "PS_EINVAL", 2: "PS_ENOMEM", 3: "PS_ESTATE", 4: "PS_EFULL", 5: "PS_EDEVICE"}
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libps_hotpath.so")
+
+EXPORTS = ["ps_workspace_bytes", "ps_init", "ps_destroy", "ps_sync", "ps_set_weights", "ps_get_weights",
+           "ps_snapshot_weights", "worker_grads_batched", "ps_queue_push_host", "ps_apply_sync", "ps_apply_async",
+           "ps_drain_buffered", "ps_get_grad", "ps_queue_meta", "ps_version", "ps_debug_last_batch", "ps_profile_enable", "ps_profile_read", "ps_profile_kernel_count",
+           "ps_profile_kernel_name", "ps_last_error"]
+
+
+class PsError(RuntimeError):
+    def __init__(self, call: str, status: int, message: str = ""):
+        super().__init__(f"{call}: {_STATUS.get(status, status)} {message}".strip())
+        self.status = status
+
+
+class ps_config(ctypes.Structure):
+    _fields_ = [("max_workers", ctypes.c_int32), ("batch", ctypes.c_int32), ("n_versions", ctypes.c_int32),
+                ("queue_capacity", ctypes.c_int32), ("seed", ctypes.c_uint64), ("dropout_p", ctypes.c_float)]
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Loads the in-tree HIP library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        lib = ctypes.CDLL(LIB_PATH)
+        vp, i32, u64, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_uint64, ctypes.c_float
+        sig = {
+            "ps_workspace_bytes": [ctypes.POINTER(ps_config), ctypes.POINTER(u64)],
+            "ps_init": [ctypes.POINTER(vp), ctypes.POINTER(ps_config), vp, u64, vp],
+            "ps_destroy": [vp], "ps_sync": [vp],
+            "ps_set_weights": [vp, vp], "ps_get_weights": [vp, i32, vp],
+            "ps_snapshot_weights": [vp, i32, ctypes.POINTER(u64)],
+            "worker_grads_batched": [vp, i32, vp, vp, vp, vp, vp, vp, vp],
+            "ps_queue_push_host": [vp, vp, i32, u64, u64, ctypes.POINTER(i32)],
+            "ps_apply_sync": [vp, vp, i32, f32], "ps_apply_async": [vp, i32, f32],
+            "ps_drain_buffered": [vp, i32, f32, ctypes.POINTER(i32)],
+            "ps_get_grad": [vp, i32, vp],
+            "ps_queue_meta": [vp, i32, ctypes.POINTER(i32), vp, vp, vp, vp, vp],
+            "ps_version": [vp, ctypes.POINTER(u64)],
+            "ps_debug_last_batch": [vp, i32, vp, vp, vp, vp, vp, vp],
+            "ps_profile_enable": [vp, i32],
+            "ps_profile_read": [vp, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)],
+        }
+        for name, args in sig.items():
+            fn = getattr(lib, name)
+            fn.argtypes = args
+            fn.restype = ctypes.c_int
+        lib.ps_profile_kernel_count.argtypes = []
+        lib.ps_profile_kernel_count.restype = ctypes.c_int32
+        lib.ps_profile_kernel_name.argtypes = [i32]
+        lib.ps_profile_kernel_name.restype = ctypes.c_char_p
+        lib.ps_last_error.argtypes = [vp]
+        lib.ps_last_error.restype = ctypes.c_char_p
+        _lib = lib
+    return _lib
+
+
+@dataclass
+class Context:
+    """Handle of one ps_ctx plus the torch tensor that owns its device workspace."""
+    handle: ctypes.c_void_p
+    workspace: object
+    cfg: ps_config
+    closed: bool = False
+
+
+def _check(ctx: Optional[Context], call: str, status: int) -> None:
+    if status != PS_OK:
+        msg = ""
+        if ctx is not None and ctx.handle:
+            msg = (load_library().ps_last_error(ctx.handle) or b"").decode()
+        raise PsError(call, status, msg)
+
+
+def _np(a, dtype) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+def _vp(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def make_config(max_workers: int, batch: int, n_versions: int, queue_capacity: int, seed: int,
+                dropout_p: float = 0.25) -> ps_config:
+    return ps_config(max_workers, batch, n_versions, queue_capacity, seed, dropout_p)
+
+
+def ps_workspace_bytes(cfg: ps_config) -> int:
+    out = ctypes.c_uint64(0)
+    _check(None, "ps_workspace_bytes", load_library().ps_workspace_bytes(ctypes.byref(cfg), ctypes.byref(out)))
+    return int(out.value)
+
+
+def ps_init(cfg: ps_config, device: str = "cuda:0") -> Context:
+    """Allocates the workspace with torch on `device` and creates the context on torch's current stream."""
+    import torch
+    lib = load_library()
+    nbytes = ps_workspace_bytes(cfg)
+    dev = torch.device(device)
+    torch.cuda.set_device(dev)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    handle = ctypes.c_void_p()
+    stream = torch.cuda.current_stream(dev).cuda_stream
+    st = lib.ps_init(ctypes.byref(handle), ctypes.byref(cfg), ctypes.c_void_p(ws.data_ptr()), nbytes,
+                     ctypes.c_void_p(stream))
+    _check(None, "ps_init", st)
+    return Context(handle, ws, cfg)
+
+
+def ps_destroy(ctx: Context) -> None:
+    if not ctx.closed:
+        _check(ctx, "ps_destroy", load_library().ps_destroy(ctx.handle))
+        ctx.closed = True
+        ctx.workspace = None
+
+
+def ps_sync(ctx: Context) -> None:
+    _check(ctx, "ps_sync", load_library().ps_sync(ctx.handle))
+
+
+def ps_set_weights(ctx: Context, theta: np.ndarray) -> None:
+    theta = _np(theta, np.float32)
+    assert theta.shape == (P,)
+    _check(ctx, "ps_set_weights", load_library().ps_set_weights(ctx.handle, _vp(theta)))
+
+
+def ps_get_weights(ctx: Context, slot: int = -1) -> np.ndarray:
+    out = np.empty(P, dtype=np.float32)
+    _check(ctx, "ps_get_weights", load_library().ps_get_weights(ctx.handle, slot, _vp(out)))
+    return out
+
+
+def ps_snapshot_weights(ctx: Context, slot: int) -> int:
+    v = ctypes.c_uint64(0)
+    _check(ctx, "ps_snapshot_weights", load_library().ps_snapshot_weights(ctx.handle, slot, ctypes.byref(v)))
+    return int(v.value)
+
+
+def worker_grads_batched(ctx: Context, worker_id: Sequence[int], version_slot: Sequence[int],
+                         minibatch_id: Sequence[int], x_dev, y_dev, loss_dev=None) -> List[int]:
+    """x_dev: torch float32 cuda tensor [n, B, 784]; y_dev: torch int32 cuda tensor [n, B];
+    loss_dev: optional torch float32 cuda tensor [n].  Returns the queue entry of each gradient."""
+    n = len(worker_id)
+    w = _np(worker_id, np.int32)
+    s = _np(version_slot, np.int32)
+    m = _np(minibatch_id, np.uint64)
+    assert w.shape == s.shape == m.shape == (n,)
+    if n:
+        import torch
+        B = ctx.cfg.batch
+        assert x_dev.is_cuda and x_dev.dtype == torch.float32 and x_dev.is_contiguous()
+        assert y_dev.is_cuda and y_dev.dtype == torch.int32 and y_dev.is_contiguous()
+        assert x_dev.numel() == n * B * IMAGE_PIXELS and y_dev.numel() == n * B
+        assert loss_dev is None or (loss_dev.is_cuda and loss_dev.dtype == torch.float32 and loss_dev.numel() >= n)
+    q = np.full(n, -1, dtype=np.int32)
+    st = load_library().worker_grads_batched(
+        ctx.handle, n, _vp(w), _vp(s), _vp(m),
+        ctypes.c_void_p(x_dev.data_ptr()) if n else None, ctypes.c_void_p(y_dev.data_ptr()) if n else None, _vp(q),
+        ctypes.c_void_p(loss_dev.data_ptr()) if loss_dev is not None else None)
+    _check(ctx, "worker_grads_batched", st)
+    return [int(v) for v in q]
+
+
+def ps_queue_push_host(ctx: Context, grad: np.ndarray, worker_id: int, version: int, minibatch_id: int) -> int:
+    grad = _np(grad, np.float32)
+    assert grad.shape == (P,)
+    q = ctypes.c_int32(-1)
+    st = load_library().ps_queue_push_host(ctx.handle, _vp(grad), worker_id, version, minibatch_id, ctypes.byref(q))
+    _check(ctx, "ps_queue_push_host", st)
+    return int(q.value)
+
+
+def ps_apply_sync(ctx: Context, queue_index: Sequence[int], lr: float) -> None:
+    q = _np(queue_index, np.int32)
+    _check(ctx, "ps_apply_sync", load_library().ps_apply_sync(ctx.handle, _vp(q), len(q), lr))
+
+
+def ps_apply_async(ctx: Context, queue_index: int, lr: float) -> None:
+    _check(ctx, "ps_apply_async", load_library().ps_apply_async(ctx.handle, queue_index, lr))
+
+
+def ps_drain_buffered(ctx: Context, mode: int, lr: float) -> int:
+    k = ctypes.c_int32(0)
+    _check(ctx, "ps_drain_buffered", load_library().ps_drain_buffered(ctx.handle, mode, lr, ctypes.byref(k)))
+    return int(k.value)
+
+
+def ps_get_grad(ctx: Context, queue_index: int) -> np.ndarray:
+    out = np.empty(P, dtype=np.float32)
+    _check(ctx, "ps_get_grad", load_library().ps_get_grad(ctx.handle, queue_index, _vp(out)))
+    return out
+
+
+def ps_queue_meta(ctx: Context) -> List[Tuple[int, int, int, int, int]]:
+    """Pending entries in arrival order as (seq, worker, version, minibatch_id, queue_index)."""
+    cap = ctx.cfg.queue_capacity
+    n = ctypes.c_int32(0)
+    seq, ver, mb = (np.zeros(cap, np.uint64) for _ in range(3))
+    wk, qi = (np.zeros(cap, np.int32) for _ in range(2))
+    st = load_library().ps_queue_meta(ctx.handle, cap, ctypes.byref(n), _vp(seq), _vp(wk), _vp(ver), _vp(mb), _vp(qi))
+    _check(ctx, "ps_queue_meta", st)
+    return [(int(seq[i]), int(wk[i]), int(ver[i]), int(mb[i]), int(qi[i])) for i in range(n.value)]
+
+
+def ps_version(ctx: Context) -> int:
+    v = ctypes.c_uint64(0)
+    _check(ctx, "ps_version", load_library().ps_version(ctx.handle, ctypes.byref(v)))
+    return int(v.value)
+
+
+def ps_debug_last_batch(ctx: Context, i: int) -> dict:
+    B = ctx.cfg.batch
+    out = {"pool1": np.empty((B, POOL1_SIZE), np.uint8), "pool2": np.empty((B, POOL2_SIZE), np.uint8),
+           "keep": np.empty((B, FC1_UNITS), np.uint8), "hdrop": np.empty((B, FC1_UNITS), np.float32),
+           "z": np.empty((B, N_CLASSES), np.float32), "pred": np.empty(B, np.int32)}
+    st = load_library().ps_debug_last_batch(ctx.handle, i, _vp(out["pool1"]), _vp(out["pool2"]), _vp(out["keep"]),
+                                            _vp(out["hdrop"]), _vp(out["z"]), _vp(out["pred"]))
+    _check(ctx, "ps_debug_last_batch", st)
+    return out
+
+
+def ps_profile_enable(ctx: Context, enable: bool) -> None:
+    _check(ctx, "ps_profile_enable", load_library().ps_profile_enable(ctx.handle, 1 if enable else 0))
+
+
+def ps_profile_read(ctx: Context) -> dict:
+    """{kernel name: (total milliseconds, launches)} since timing was last enabled."""
+    lib = load_library()
+    out = {}
+    for k in range(lib.ps_profile_kernel_count()):
+        ms, n = ctypes.c_double(0.0), ctypes.c_int64(0)
+        _check(ctx, "ps_profile_read", lib.ps_profile_read(ctx.handle, k, ctypes.byref(ms), ctypes.byref(n)))
+        out[lib.ps_profile_kernel_name(k).decode()] = (float(ms.value), int(n.value))
+    return out

@@ -1,0 +1,478 @@
+// C ABI of the parameter-server hot path (see include/ps_hotpath.h for the contract) and the host
+// side of the pending-gradient queue: which entries are free, which are pending and in what
+// arrival order, and which snapshot version each gradient was computed on (Section 3.3: gradients
+// are written once by a worker, read once by the server and deleted after they are applied).
+#include "../../include/ps_hotpath.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "ps_common.h"
+
+using namespace ps;
+
+static_assert(PS_PARAM_COUNT == P, "header and kernels disagree on the parameter count");
+
+namespace {
+
+constexpr int N_STAGE = 4;  // pinned host staging buffers for per-call index / metadata uploads
+
+struct Entry {
+    bool pending = false;
+    uint64_t seq = 0, version = 0, mb = 0;
+    int32_t worker = 0;
+};
+
+struct Stage {
+    void* host = nullptr;
+    hipEvent_t done = nullptr;
+    bool in_flight = false;
+};
+
+struct Carve {
+    uint64_t off = 0;
+    uint64_t take(uint64_t bytes)
+    {
+        const uint64_t at = off;
+        off += (bytes + 255) & ~uint64_t(255);
+        return at;
+    }
+};
+
+struct Layout {
+    uint64_t theta, ring, queue, meta, idx, p1, am1, p2, am2, ht, z, pred, loss_i, d4, d3, dp2g, dp1g, part, keep, total;
+};
+
+bool config_ok(const ps_config* c)
+{
+    return c && c->max_workers >= 1 && c->batch >= 1 && c->n_versions >= 1 && c->queue_capacity >= 1 &&
+           c->dropout_p >= 0.f && c->dropout_p < 1.f && (int64_t)c->max_workers * c->batch <= (int64_t)1 << 24;
+}
+
+Layout make_layout(const ps_config& c)
+{
+    const uint64_t n = (uint64_t)c.max_workers * c.batch, row = (uint64_t)PSTRIDE * sizeof(float);
+    Carve k;
+    Layout l;
+    l.theta = k.take(row);
+    l.ring = k.take(row * c.n_versions);
+    l.queue = k.take(row * c.queue_capacity);
+    l.meta = k.take(sizeof(WorkerMeta) * c.max_workers);
+    l.idx = k.take(sizeof(int32_t) * c.queue_capacity);
+    l.p1 = k.take(n * P1_SIZE * 4);
+    l.am1 = k.take(n * P1_SIZE);
+    l.p2 = k.take(n * P2_SIZE * 4);
+    l.am2 = k.take(n * P2_SIZE);
+    l.ht = k.take(n * FC1 * 4);
+    l.z = k.take(n * NCLS * 4);
+    l.pred = k.take(n * 4);
+    l.loss_i = k.take(n * 4);
+    l.d4 = k.take(n * NCLS * 4);
+    l.d3 = k.take(n * FC1 * 4);
+    l.dp2g = k.take(n * P2_SIZE * 4);
+    l.dp1g = k.take(n * P1_SIZE * 4);
+    l.part = k.take((uint64_t)c.max_workers * N_CHUNK * CONV_PART * 4);
+    l.keep = k.take((uint64_t)c.batch * FC1);
+    l.total = k.off;
+    return l;
+}
+
+}  // namespace
+
+struct ps_ctx {
+    ps_config cfg{};
+    hipStream_t stream = nullptr;
+    char* ws = nullptr;
+    Layout lay{};
+    std::vector<Entry> entries;
+    std::vector<int32_t> free_list;  // stack; lowest index on top
+    std::vector<int32_t> pending;    // queue indices in arrival order
+    std::vector<uint64_t> ring_version;
+    std::vector<WorkerMeta> last_meta;
+    uint64_t version = 0, next_seq = 0;
+    Stage stage[N_STAGE];
+    int next_stage = 0;
+    size_t stage_bytes = 0;
+    Profiler prof;
+    std::string err;
+
+    template <class T>
+    T* at(uint64_t off) const { return reinterpret_cast<T*>(ws + off); }
+    float* theta() const { return at<float>(lay.theta); }
+    float* ring(int slot) const { return at<float>(lay.ring) + (size_t)slot * PSTRIDE; }
+    float* queue(int q) const { return at<float>(lay.queue) + (size_t)q * PSTRIDE; }
+};
+
+namespace {
+
+ps_status fail(ps_ctx* c, ps_status st, const std::string& msg)
+{
+    if (c) c->err = msg;
+    return st;
+}
+
+#define PS_HIP(ctx, call)                                                                           \
+    do {                                                                                            \
+        hipError_t e_ = (call);                                                                     \
+        if (e_ != hipSuccess)                                                                       \
+            return fail(ctx, PS_EDEVICE, std::string(#call) + ": " + hipGetErrorString(e_));        \
+    } while (0)
+
+// Copies `bytes` of host data to `dst_dev` through a pinned staging buffer, asynchronously.
+ps_status upload(ps_ctx* c, void* dst_dev, const void* src, size_t bytes)
+{
+    if (bytes == 0) return PS_OK;
+    Stage& s = c->stage[c->next_stage];
+    c->next_stage = (c->next_stage + 1) % N_STAGE;
+    if (s.in_flight) PS_HIP(c, hipEventSynchronize(s.done));
+    std::memcpy(s.host, src, bytes);
+    PS_HIP(c, hipMemcpyAsync(dst_dev, s.host, bytes, hipMemcpyHostToDevice, c->stream));
+    PS_HIP(c, hipEventRecord(s.done, c->stream));
+    s.in_flight = true;
+    return PS_OK;
+}
+
+ps_status apply_entries(ps_ctx* c, const std::vector<int32_t>& idx, float lr, int mode)
+{
+    ps_status st = upload(c, c->at<int32_t>(c->lay.idx), idx.data(), idx.size() * sizeof(int32_t));
+    if (st != PS_OK) return st;
+    PS_HIP(c, launch_apply(c->theta(), c->at<float>(c->lay.queue), c->at<int32_t>(c->lay.idx), (int)idx.size(), lr,
+                           mode, c->stream, c->prof));
+    return PS_OK;
+}
+
+void release_entries(ps_ctx* c, const std::vector<int32_t>& idx)
+{
+    for (int32_t q : idx) c->entries[q].pending = false;
+    std::vector<int32_t> keep;
+    keep.reserve(c->pending.size());
+    for (int32_t q : c->pending)
+        if (c->entries[q].pending) keep.push_back(q);
+    c->pending.swap(keep);
+    // Freed entries go back so that the lowest index is handed out first.
+    for (int32_t q : idx) c->free_list.push_back(q);
+    std::sort(c->free_list.begin(), c->free_list.end(), [](int32_t a, int32_t b) { return a > b; });
+}
+
+int32_t take_entry(ps_ctx* c, int32_t worker, uint64_t version, uint64_t mb)
+{
+    const int32_t q = c->free_list.back();
+    c->free_list.pop_back();
+    Entry& e = c->entries[q];
+    e.pending = true;
+    e.seq = c->next_seq++;
+    e.worker = worker;
+    e.version = version;
+    e.mb = mb;
+    c->pending.push_back(q);
+    return q;
+}
+
+WorkerBuffers buffers(const ps_ctx* c, int n, const float* x, const int32_t* y, float* loss)
+{
+    WorkerBuffers wb{};
+    wb.ring = c->at<float>(c->lay.ring);
+    wb.queue = c->at<float>(c->lay.queue);
+    wb.meta = c->at<WorkerMeta>(c->lay.meta);
+    wb.x = x;
+    wb.y = y;
+    wb.p1 = c->at<float>(c->lay.p1);
+    wb.am1 = c->at<uint8_t>(c->lay.am1);
+    wb.p2 = c->at<float>(c->lay.p2);
+    wb.am2 = c->at<uint8_t>(c->lay.am2);
+    wb.ht = c->at<float>(c->lay.ht);
+    wb.z = c->at<float>(c->lay.z);
+    wb.pred = c->at<int32_t>(c->lay.pred);
+    wb.loss_i = c->at<float>(c->lay.loss_i);
+    wb.d4 = c->at<float>(c->lay.d4);
+    wb.d3 = c->at<float>(c->lay.d3);
+    wb.dp2g = c->at<float>(c->lay.dp2g);
+    wb.dp1g = c->at<float>(c->lay.dp1g);
+    wb.part = c->at<float>(c->lay.part);
+    wb.loss = loss;
+    wb.n = n;
+    wb.B = c->cfg.batch;
+    wb.seed_lo = (uint32_t)c->cfg.seed;
+    wb.seed_hi = (uint32_t)(c->cfg.seed >> 32);
+    wb.drop_threshold = (uint32_t)std::floor((double)c->cfg.dropout_p * 4294967296.0);
+    wb.drop_scale = (float)(1.0 / (1.0 - (double)c->cfg.dropout_p));
+    return wb;
+}
+
+}  // namespace
+
+extern "C" {
+
+ps_status ps_workspace_bytes(const ps_config* cfg, uint64_t* bytes_out)
+{
+    if (!bytes_out || !config_ok(cfg)) return PS_EINVAL;
+    *bytes_out = make_layout(*cfg).total;
+    return PS_OK;
+}
+
+ps_status ps_init(ps_ctx** out, const ps_config* cfg, void* workspace_dev, uint64_t workspace_bytes, void* hip_stream)
+{
+    if (!out) return PS_EINVAL;
+    *out = nullptr;
+    if (!config_ok(cfg) || !workspace_dev || (reinterpret_cast<uintptr_t>(workspace_dev) & 255)) return PS_EINVAL;
+    const Layout lay = make_layout(*cfg);
+    if (workspace_bytes < lay.total) return PS_ENOMEM;
+    ps_ctx* c = new (std::nothrow) ps_ctx;
+    if (!c) return PS_ENOMEM;
+    c->cfg = *cfg;
+    c->stream = static_cast<hipStream_t>(hip_stream);
+    c->ws = static_cast<char*>(workspace_dev);
+    c->lay = lay;
+    c->entries.assign(cfg->queue_capacity, Entry{});
+    for (int32_t q = cfg->queue_capacity - 1; q >= 0; --q) c->free_list.push_back(q);
+    c->ring_version.assign(cfg->n_versions, 0);
+    c->stage_bytes = std::max(sizeof(WorkerMeta) * (size_t)cfg->max_workers, sizeof(int32_t) * (size_t)cfg->queue_capacity);
+    hipError_t e = hipSuccess;
+    for (int i = 0; i < N_STAGE && e == hipSuccess; ++i) {
+        e = hipHostMalloc(&c->stage[i].host, c->stage_bytes, hipHostMallocDefault);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&c->stage[i].done, hipEventDisableTiming);
+    }
+    // Weights, ring, queue (padding included) and the index arrays start at zero.
+    if (e == hipSuccess) e = hipMemsetAsync(c->ws, 0, lay.p1, c->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+    if (e != hipSuccess) {
+        std::fprintf(stderr, "ps_init: %s\n", hipGetErrorString(e));
+        ps_destroy(c);
+        return PS_EDEVICE;
+    }
+    *out = c;
+    return PS_OK;
+}
+
+ps_status ps_destroy(ps_ctx* c)
+{
+    if (!c) return PS_EINVAL;
+    (void)hipStreamSynchronize(c->stream);
+    c->prof.destroy();
+    for (Stage& s : c->stage) {
+        if (s.done) (void)hipEventDestroy(s.done);
+        if (s.host) (void)hipHostFree(s.host);
+    }
+    delete c;
+    return PS_OK;
+}
+
+ps_status ps_sync(ps_ctx* c)
+{
+    if (!c) return PS_EINVAL;
+    PS_HIP(c, hipStreamSynchronize(c->stream));
+    return PS_OK;
+}
+
+ps_status ps_set_weights(ps_ctx* c, const float* theta_host)
+{
+    if (!c || !theta_host) return fail(c, PS_EINVAL, "ps_set_weights: null argument");
+    if (!c->pending.empty()) return fail(c, PS_ESTATE, "ps_set_weights: queue not empty");
+    PS_HIP(c, hipMemcpyAsync(c->theta(), theta_host, sizeof(float) * P, hipMemcpyHostToDevice, c->stream));
+    for (int s = 0; s < c->cfg.n_versions; ++s) {
+        PS_HIP(c, hipMemcpyAsync(c->ring(s), c->theta(), sizeof(float) * PSTRIDE, hipMemcpyDeviceToDevice, c->stream));
+        c->ring_version[s] = 0;
+    }
+    PS_HIP(c, hipStreamSynchronize(c->stream));
+    c->version = 0;
+    return PS_OK;
+}
+
+ps_status ps_get_weights(ps_ctx* c, int32_t slot, float* theta_host)
+{
+    if (!c || !theta_host) return fail(c, PS_EINVAL, "ps_get_weights: null argument");
+    if (slot < -1 || slot >= c->cfg.n_versions) return fail(c, PS_EINVAL, "ps_get_weights: slot out of range");
+    const float* src = slot < 0 ? c->theta() : c->ring(slot);
+    PS_HIP(c, hipMemcpyAsync(theta_host, src, sizeof(float) * P, hipMemcpyDeviceToHost, c->stream));
+    PS_HIP(c, hipStreamSynchronize(c->stream));
+    return PS_OK;
+}
+
+ps_status ps_snapshot_weights(ps_ctx* c, int32_t slot, uint64_t* version_out)
+{
+    if (!c) return PS_EINVAL;
+    if (slot < 0 || slot >= c->cfg.n_versions) return fail(c, PS_EINVAL, "ps_snapshot_weights: slot out of range");
+    PS_HIP(c, hipMemcpyAsync(c->ring(slot), c->theta(), sizeof(float) * PSTRIDE, hipMemcpyDeviceToDevice, c->stream));
+    c->ring_version[slot] = c->version;
+    if (version_out) *version_out = c->version;
+    return PS_OK;
+}
+
+ps_status worker_grads_batched(ps_ctx* c, int32_t n, const int32_t* worker_id_host, const int32_t* version_slot_host,
+                               const uint64_t* minibatch_id_host, const float* x_dev, const int32_t* y_dev,
+                               int32_t* queue_index_host, float* loss_dev)
+{
+    if (!c) return PS_EINVAL;
+    if (n == 0) return PS_OK;
+    if (n < 0 || n > c->cfg.max_workers) return fail(c, PS_EINVAL, "worker_grads_batched: n outside [0, max_workers]");
+    if (!worker_id_host || !version_slot_host || !minibatch_id_host || !x_dev || !y_dev || !queue_index_host)
+        return fail(c, PS_EINVAL, "worker_grads_batched: null argument");
+    if ((reinterpret_cast<uintptr_t>(x_dev) & 15) || (reinterpret_cast<uintptr_t>(y_dev) & 3))
+        return fail(c, PS_EINVAL, "worker_grads_batched: x_dev must be 16-byte and y_dev 4-byte aligned");
+    for (int i = 0; i < n; ++i)
+        if (version_slot_host[i] < 0 || version_slot_host[i] >= c->cfg.n_versions)
+            return fail(c, PS_EINVAL, "worker_grads_batched: version slot out of range");
+    if ((size_t)n > c->free_list.size()) return fail(c, PS_EFULL, "worker_grads_batched: gradient queue full");
+
+    c->last_meta.resize(n);
+    for (int i = 0; i < n; ++i) {
+        const int32_t slot = version_slot_host[i];
+        const uint64_t mb = minibatch_id_host[i];
+        const int32_t q = take_entry(c, worker_id_host[i], c->ring_version[slot], mb);
+        queue_index_host[i] = q;
+        c->last_meta[i] = WorkerMeta{slot, q, (uint32_t)mb, (uint32_t)(mb >> 32)};
+    }
+    ps_status st = upload(c, c->at<WorkerMeta>(c->lay.meta), c->last_meta.data(), sizeof(WorkerMeta) * n);
+    if (st != PS_OK) return st;
+    const WorkerBuffers wb = buffers(c, n, x_dev, y_dev, loss_dev);
+    PS_HIP(c, launch_worker_forward(wb, c->stream, c->prof));
+    PS_HIP(c, launch_worker_backward(wb, c->stream, c->prof));
+    return PS_OK;
+}
+
+ps_status ps_queue_push_host(ps_ctx* c, const float* grad_host, int32_t worker_id, uint64_t version,
+                             uint64_t minibatch_id, int32_t* queue_index_host)
+{
+    if (!c || !grad_host || !queue_index_host) return fail(c, PS_EINVAL, "ps_queue_push_host: null argument");
+    if (c->free_list.empty()) return fail(c, PS_EFULL, "ps_queue_push_host: gradient queue full");
+    const int32_t q = take_entry(c, worker_id, version, minibatch_id);
+    *queue_index_host = q;
+    PS_HIP(c, hipMemcpyAsync(c->queue(q), grad_host, sizeof(float) * P, hipMemcpyHostToDevice, c->stream));
+    PS_HIP(c, hipStreamSynchronize(c->stream));
+    return PS_OK;
+}
+
+ps_status ps_apply_sync(ps_ctx* c, const int32_t* queue_index_host, int32_t n, float lr)
+{
+    if (!c) return PS_EINVAL;
+    if (n == 0) return PS_OK;
+    if (n < 0 || !queue_index_host) return fail(c, PS_EINVAL, "ps_apply_sync: bad arguments");
+    std::vector<int32_t> idx(queue_index_host, queue_index_host + n);
+    std::vector<char> seen(c->cfg.queue_capacity, 0);
+    for (int32_t q : idx) {
+        if (q < 0 || q >= c->cfg.queue_capacity) return fail(c, PS_EINVAL, "ps_apply_sync: queue index out of range");
+        if (!c->entries[q].pending || seen[q]) return fail(c, PS_ESTATE, "ps_apply_sync: entry not pending or listed twice");
+        seen[q] = 1;
+    }
+    ps_status st = apply_entries(c, idx, lr, PS_DRAIN_SUM);
+    if (st != PS_OK) return st;
+    release_entries(c, idx);
+    c->version += 1;
+    return PS_OK;
+}
+
+ps_status ps_apply_async(ps_ctx* c, int32_t q, float lr)
+{
+    if (!c) return PS_EINVAL;
+    if (q < 0 || q >= c->cfg.queue_capacity) return fail(c, PS_EINVAL, "ps_apply_async: queue index out of range");
+    if (!c->entries[q].pending) return fail(c, PS_ESTATE, "ps_apply_async: entry not pending");
+    const std::vector<int32_t> idx{q};
+    ps_status st = apply_entries(c, idx, lr, PS_DRAIN_SEQ);
+    if (st != PS_OK) return st;
+    release_entries(c, idx);
+    c->version += 1;
+    return PS_OK;
+}
+
+ps_status ps_drain_buffered(ps_ctx* c, int32_t mode, float lr, int32_t* n_applied_host)
+{
+    if (!c) return PS_EINVAL;
+    if (mode != PS_DRAIN_SUM && mode != PS_DRAIN_SEQ) return fail(c, PS_EINVAL, "ps_drain_buffered: unknown mode");
+    const std::vector<int32_t> idx = c->pending;
+    if (n_applied_host) *n_applied_host = (int32_t)idx.size();
+    if (idx.empty()) return PS_OK;
+    ps_status st = apply_entries(c, idx, lr, mode);
+    if (st != PS_OK) return st;
+    release_entries(c, idx);
+    c->version += mode == PS_DRAIN_SUM ? 1 : idx.size();
+    return PS_OK;
+}
+
+ps_status ps_get_grad(ps_ctx* c, int32_t q, float* grad_host)
+{
+    if (!c || !grad_host) return fail(c, PS_EINVAL, "ps_get_grad: null argument");
+    if (q < 0 || q >= c->cfg.queue_capacity) return fail(c, PS_EINVAL, "ps_get_grad: queue index out of range");
+    if (!c->entries[q].pending) return fail(c, PS_ESTATE, "ps_get_grad: entry not pending");
+    PS_HIP(c, hipMemcpyAsync(grad_host, c->queue(q), sizeof(float) * P, hipMemcpyDeviceToHost, c->stream));
+    PS_HIP(c, hipStreamSynchronize(c->stream));
+    return PS_OK;
+}
+
+ps_status ps_queue_meta(ps_ctx* c, int32_t capacity, int32_t* n_host, uint64_t* seq_host, int32_t* worker_host,
+                        uint64_t* version_host, uint64_t* minibatch_host, int32_t* queue_index_host)
+{
+    if (!c || !n_host || capacity < 0) return fail(c, PS_EINVAL, "ps_queue_meta: bad arguments");
+    *n_host = (int32_t)c->pending.size();
+    const int m = std::min<int>(capacity, (int)c->pending.size());
+    for (int i = 0; i < m; ++i) {
+        const int32_t q = c->pending[i];
+        const Entry& e = c->entries[q];
+        if (seq_host) seq_host[i] = e.seq;
+        if (worker_host) worker_host[i] = e.worker;
+        if (version_host) version_host[i] = e.version;
+        if (minibatch_host) minibatch_host[i] = e.mb;
+        if (queue_index_host) queue_index_host[i] = q;
+    }
+    return PS_OK;
+}
+
+ps_status ps_version(ps_ctx* c, uint64_t* version_host)
+{
+    if (!c || !version_host) return PS_EINVAL;
+    *version_host = c->version;
+    return PS_OK;
+}
+
+ps_status ps_debug_last_batch(ps_ctx* c, int32_t i, uint8_t* pool1_host, uint8_t* pool2_host, uint8_t* keep_host,
+                              float* hdrop_host, float* z_host, int32_t* pred_host)
+{
+    if (!c) return PS_EINVAL;
+    if (i < 0 || i >= (int32_t)c->last_meta.size()) return fail(c, PS_EINVAL, "ps_debug_last_batch: no such worker in the last call");
+    const size_t B = c->cfg.batch, g0 = (size_t)i * B;
+    hipStream_t s = c->stream;
+    if (pool1_host) PS_HIP(c, hipMemcpyAsync(pool1_host, c->at<uint8_t>(c->lay.am1) + g0 * P1_SIZE, B * P1_SIZE, hipMemcpyDeviceToHost, s));
+    if (pool2_host) PS_HIP(c, hipMemcpyAsync(pool2_host, c->at<uint8_t>(c->lay.am2) + g0 * P2_SIZE, B * P2_SIZE, hipMemcpyDeviceToHost, s));
+    if (hdrop_host) PS_HIP(c, hipMemcpyAsync(hdrop_host, c->at<float>(c->lay.ht) + g0 * FC1, B * FC1 * 4, hipMemcpyDeviceToHost, s));
+    if (z_host) PS_HIP(c, hipMemcpyAsync(z_host, c->at<float>(c->lay.z) + g0 * NCLS, B * NCLS * 4, hipMemcpyDeviceToHost, s));
+    if (pred_host) PS_HIP(c, hipMemcpyAsync(pred_host, c->at<int32_t>(c->lay.pred) + g0, B * 4, hipMemcpyDeviceToHost, s));
+    if (keep_host) {
+        const WorkerMeta& m = c->last_meta[i];
+        const WorkerBuffers wb = buffers(c, 0, nullptr, nullptr, nullptr);
+        PS_HIP(c, launch_keep_mask(c->at<uint8_t>(c->lay.keep), (int)B, m.mb_lo, m.mb_hi, wb.seed_lo, wb.seed_hi,
+                                   wb.drop_threshold, s));
+        PS_HIP(c, hipMemcpyAsync(keep_host, c->at<uint8_t>(c->lay.keep), B * FC1, hipMemcpyDeviceToHost, s));
+    }
+    PS_HIP(c, hipStreamSynchronize(s));
+    return PS_OK;
+}
+
+ps_status ps_profile_enable(ps_ctx* c, int32_t enable)
+{
+    if (!c) return PS_EINVAL;
+    PS_HIP(c, c->prof.collect(c->stream));
+    c->prof.reset();
+    c->prof.enabled = enable != 0;
+    return PS_OK;
+}
+
+ps_status ps_profile_read(ps_ctx* c, int32_t kernel_id, double* total_ms_host, int64_t* launches_host)
+{
+    if (!c || kernel_id < 0 || kernel_id >= K_COUNT) return fail(c, PS_EINVAL, "ps_profile_read: no such kernel");
+    PS_HIP(c, c->prof.collect(c->stream));
+    if (total_ms_host) *total_ms_host = c->prof.total_ms[kernel_id];
+    if (launches_host) *launches_host = c->prof.launches[kernel_id];
+    return PS_OK;
+}
+
+int32_t ps_profile_kernel_count(void) { return K_COUNT; }
+
+const char* ps_profile_kernel_name(int32_t kernel_id) { return kernel_name(kernel_id); }
+
+const char* ps_last_error(const ps_ctx* c) { return c ? c->err.c_str() : ""; }
+
+}  // extern "C"

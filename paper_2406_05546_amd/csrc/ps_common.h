@@ -1,0 +1,95 @@
+// Shared declarations of the HIP implementation: network sizes (paper's model endnote), the flat
+// parameter layout, per-worker call metadata and the launchers the C ABI drives.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <vector>
+
+namespace ps {
+
+constexpr int IMG_W = 28, IMG_PIX = 784;
+constexpr int C1 = 16, C2 = 32;
+constexpr int P1_W = 14, P1_POS = 196, P1_SIZE = C1 * P1_POS;  // 3136
+constexpr int P2_W = 7, P2_POS = 49, P2_SIZE = C2 * P2_POS;    // 1568
+constexpr int FC1 = 512, NCLS = 10;
+
+constexpr int OFF_W1 = 0, OFF_B1 = 144, OFF_W2 = 160, OFF_B2 = 4768, OFF_W3 = 4800, OFF_B3 = 807616,
+              OFF_W4 = 808128, OFF_B4 = 813248, P = 813258;
+// Row pitch of every P-vector in HBM (weights, ring slots, queue entries): P rounded up to 256 B.
+constexpr int PSTRIDE = 813312;
+constexpr int CONV_PART = OFF_W3;  // conv1 + conv2 gradient floats (4800), reduced from chunk partials
+constexpr int N_CHUNK = 8;         // image chunks per worker in the conv weight-gradient reductions
+
+// One worker of a batched call.
+struct WorkerMeta {
+    int32_t slot;    // ring slot of the snapshot it reads
+    int32_t q;       // queue entry its gradient goes to
+    uint32_t mb_lo;  // logical minibatch id (dropout counter words 0, 1)
+    uint32_t mb_hi;
+};
+
+// Device buffers of one batched worker step; activations are indexed by global image g = w*B + s.
+struct WorkerBuffers {
+    const float* ring;   // [V][PSTRIDE]
+    float* queue;        // [cap][PSTRIDE]
+    const WorkerMeta* meta;  // [n]
+    const float* x;      // [n*B][784]
+    const int32_t* y;    // [n*B]
+    float* p1;           // [n*B][16][196]  conv1 -> ReLU -> pool
+    uint8_t* am1;        // [n*B][16][196]  bits 0-1 window winner, bit 2 winner > 0
+    float* p2;           // [n*B][32][49]
+    uint8_t* am2;        // [n*B][32][49]
+    float* ht;           // [n*B][512]      fc1 -> ReLU -> dropout
+    float* z;            // [n*B][10]       logits
+    int32_t* pred;       // [n*B]
+    float* loss_i;       // [n*B]
+    float* d4;           // [n*B][10]       d loss / d logits (already / B)
+    float* d3;           // [n*B][512]      d loss / d fc1 pre-activation
+    float* dp2g;         // [n*B][1568]     d loss / d pool2, zero where pool2 == 0
+    float* dp1g;         // [n*B][3136]     d loss / d pool1, zero where pool1 == 0
+    float* part;         // [n][N_CHUNK][4800] chunk partials of conv1/conv2 weight gradients
+    float* loss;         // [n] or nullptr
+    int32_t n, B;
+    uint32_t seed_lo, seed_hi;
+    uint32_t drop_threshold;  // drop iff word < threshold
+    float drop_scale;         // 1/(1-p)
+};
+
+// Kernels of the path, in launch order; ids index the per-kernel timing table.
+enum KernelId {
+    K_CONV1_FWD, K_CONV2_FWD, K_FC1_FWD, K_FC2, K_FC2_GRAD, K_FC1_DW, K_FC1_DX, K_CONV2_DW, K_CONV2_DX, K_CONV1_DW,
+    K_CONV_REDUCE, K_APPLY_SUM, K_APPLY_SEQ, K_COUNT
+};
+const char* kernel_name(int id);
+
+// Optional per-kernel timing with HIP events recorded on the stream the kernels run on.
+class Profiler {
+public:
+    bool enabled = false;
+    void begin(int id, hipStream_t s);
+    void end(hipStream_t s);
+    hipError_t collect(hipStream_t s);  // waits for the stream, folds finished pairs into the totals
+    void reset();
+    void destroy();
+    double total_ms[K_COUNT] = {};
+    int64_t launches[K_COUNT] = {};
+
+private:
+    struct Rec { int id; hipEvent_t a, b; };
+    hipEvent_t take();
+    std::vector<Rec> recs_;
+    std::vector<hipEvent_t> pool_;
+    Rec open_{-1, nullptr, nullptr};
+};
+
+hipError_t launch_worker_forward(const WorkerBuffers& wb, hipStream_t s, Profiler& prof);
+hipError_t launch_worker_backward(const WorkerBuffers& wb, hipStream_t s, Profiler& prof);
+hipError_t launch_keep_mask(uint8_t* keep_dev, int B, uint32_t mb_lo, uint32_t mb_hi, uint32_t seed_lo,
+                            uint32_t seed_hi, uint32_t threshold, hipStream_t s);
+
+// theta -= lr * (sum of the K listed queue rows) [mode 0] or K successive updates [mode 1].
+hipError_t launch_apply(float* theta, const float* queue, const int32_t* idx_dev, int K, float lr, int mode,
+                        hipStream_t s, Profiler& prof);
+
+}  // namespace ps

@@ -1,0 +1,72 @@
+"""Replays a synth.Scenario through the C ABI (host-side sequencing only)."""
+from __future__ import annotations
+
+from typing import Callable, Dict, List, Optional
+
+import numpy as np
+
+from . import binding as ps
+from . import synth
+
+
+class Replay:
+    """Keeps the map arrival number -> queue entry; all arithmetic happens inside the library."""
+
+    def __init__(self, sc: synth.Scenario, data_seed: int, dropout_seed: int, theta0: np.ndarray,
+                 dropout_p: float = 0.25, device: str = "cuda:0"):
+        import torch
+        self.torch = torch
+        self.sc = sc
+        self.data_seed = data_seed
+        self.device = device
+        self.ctx = ps.ps_init(ps.make_config(sc.max_call, sc.batch, sc.n_slots, sc.queue_capacity, dropout_seed,
+                                             dropout_p), device)
+        ps.ps_set_weights(self.ctx, theta0)
+        self.entry_of: Dict[int, int] = {}
+        self.next_seq = 0
+        self.meta_log: List[tuple] = []      # (seq, worker, version, mb_id) in arrival order
+        self.losses: Dict[int, float] = {}
+
+    def close(self):
+        ps.ps_destroy(self.ctx)
+
+    def run(self, on_grads: Optional[Callable[["Replay", List[int]], None]] = None) -> np.ndarray:
+        torch = self.torch
+        for ev in self.sc.events:
+            kind = ev[0]
+            if kind == "grads":
+                _, workers, slots, mbs = ev
+                x, y = synth.minibatches(self.data_seed, mbs, self.sc.batch)
+                xd = torch.from_numpy(x).to(self.device)
+                yd = torch.from_numpy(y).to(self.device)
+                loss = torch.empty(len(workers), dtype=torch.float32, device=self.device)
+                entries = ps.worker_grads_batched(self.ctx, workers, slots, mbs, xd, yd, loss)
+                seqs = list(range(self.next_seq, self.next_seq + len(workers)))
+                self.next_seq += len(workers)
+                for s, q in zip(seqs, entries):
+                    self.entry_of[s] = q
+                by_entry = {m[4]: m for m in ps.ps_queue_meta(self.ctx)}
+                for s, q in zip(seqs, entries):
+                    m = by_entry[q]
+                    self.meta_log.append((m[0], m[1], m[2], m[3]))
+                ps.ps_sync(self.ctx)                      # x, y, loss are borrowed until the work is done
+                for s, l in zip(seqs, loss.cpu().numpy()):
+                    self.losses[s] = float(l)
+                if on_grads is not None:
+                    on_grads(self, seqs)
+            elif kind == "sync":
+                ps.ps_apply_sync(self.ctx, [self.entry_of.pop(s) for s in ev[1]], ev[2])
+            elif kind == "async":
+                ps.ps_apply_async(self.ctx, self.entry_of.pop(ev[1]), ev[2])
+            elif kind == "drain":
+                k = ps.ps_drain_buffered(self.ctx, ev[1], ev[2])
+                assert k == len(self.entry_of)
+                self.entry_of.clear()
+            elif kind == "snapshot":
+                ps.ps_snapshot_weights(self.ctx, ev[1])
+            else:
+                raise ValueError(kind)
+        return ps.ps_get_weights(self.ctx)
+
+    def grad(self, seq: int) -> np.ndarray:
+        return ps.ps_get_grad(self.ctx, self.entry_of[seq])

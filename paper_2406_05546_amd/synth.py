@@ -170,3 +170,105 @@ class OutagePlan:
     @property
     def n_buffered(self) -> int:
         return self.n_workers * self.down_steps
+
+
+# --------------------------------------------------------------------------- scenarios
+# A scenario is a list of events that both the HIP harness and the oracle harness replay:
+#   ("grads", workers, slots, mb_ids)   each listed worker computes one gradient on its slot's
+#                                       snapshot; gradients get consecutive arrival numbers (seq)
+#   ("sync", seqs, lr)                  one update with all listed gradients
+#   ("async", seq, lr)                  one update with one gradient
+#   ("drain", mode, lr)                 stateless server step over everything pending
+#   ("snapshot", slot)                  a worker pulls the current weights into a ring slot
+
+DRAIN_SUM = 0
+DRAIN_SEQ = 1
+
+
+@dataclass(frozen=True)
+class Scenario:
+    name: str
+    n_workers: int
+    batch: int
+    n_slots: int
+    queue_capacity: int
+    events: Tuple[tuple, ...]
+
+    @property
+    def max_call(self) -> int:
+        return max((len(e[1]) for e in self.events if e[0] == "grads"), default=1)
+
+    @property
+    def n_gradients(self) -> int:
+        return sum(len(e[1]) for e in self.events if e[0] == "grads")
+
+
+def scenario_sync(n_workers: int, batch: int, steps: int, lr: float) -> Scenario:
+    """Synchronous SGD: every step all workers compute on the same snapshot, the server waits for
+    all of them and updates once."""
+    ev, seq = [], 0
+    for step in range(steps):
+        ws = list(range(n_workers))
+        ev.append(("grads", ws, [0] * n_workers, [minibatch_id(w, step) for w in ws]))
+        ev.append(("sync", list(range(seq, seq + n_workers)), lr))
+        ev.append(("snapshot", 0))
+        seq += n_workers
+    return Scenario("sync", n_workers, batch, 1, n_workers, tuple(ev))
+
+
+def scenario_async(seed: int, n_workers: int, batch: int, n_arrivals: int, lr: float) -> Scenario:
+    """Asynchronous SGD with the cyclic seeded arrival order of async_cyclic_arrivals.  The W
+    gradients in flight at the start of a cycle are computed in one batched call, each on its own
+    worker's slot; they then arrive one by one, and after each arrival that worker pulls."""
+    arr = async_cyclic_arrivals(seed, n_workers, n_arrivals)
+    ev = []
+    for r0 in range(0, n_arrivals, n_workers):
+        cyc = arr[r0:r0 + n_workers]
+        ev.append(("grads", [a.worker for a in cyc], [a.slot for a in cyc], [a.mb_id for a in cyc]))
+        for a in cyc:
+            ev.append(("async", a.seq, lr))
+            ev.append(("snapshot", a.slot))
+    return Scenario("async", n_workers, batch, n_workers, n_workers, tuple(ev))
+
+
+def scenario_outage(n_workers: int, batch: int, up_steps: int, down_steps: int, lr: float,
+                    recovery_mode: int = DRAIN_SEQ, recovery_lr: float = None) -> Scenario:
+    """Stateless server: while it is up every round ends with a server step over the W new
+    gradients and a publish; while it is down rounds only append; recovery is one server step over
+    the whole backlog."""
+    plan = OutagePlan(n_workers, up_steps, down_steps)
+    ev = []
+    for r, up, ids in plan.rounds():
+        ev.append(("grads", list(range(n_workers)), [0] * n_workers, ids))
+        if up:
+            ev.append(("drain", DRAIN_SEQ, lr))
+            ev.append(("snapshot", 0))
+    ev.append(("drain", recovery_mode, lr if recovery_lr is None else recovery_lr))
+    ev.append(("snapshot", 0))
+    return Scenario("outage", n_workers, batch, 1, max(n_workers, plan.n_buffered), tuple(ev))
+
+
+def scenario_versions(n_workers: int, batch: int, n_slots: int, steps: int, lr: float) -> Scenario:
+    """Batched asynchronous steps with `n_slots` weight versions resident: worker w reads slot
+    w % n_slots; after a step's gradients have been applied one by one in worker order the new
+    weights are published into slot step % n_slots, so snapshots are 0..n_slots-1 steps stale."""
+    ev, seq = [], 0
+    for step in range(steps):
+        ws = list(range(n_workers))
+        ev.append(("grads", ws, [w % n_slots for w in ws], [minibatch_id(w, step) for w in ws]))
+        for i in range(n_workers):
+            ev.append(("async", seq + i, lr))
+        ev.append(("snapshot", step % n_slots))
+        seq += n_workers
+    return Scenario("versions", n_workers, batch, n_slots, n_workers, tuple(ev))
+
+
+def paper_configs() -> dict:
+    """The five evaluation configurations (sizes fixed by this build; the paper states none)."""
+    return {
+        "sync_w2_b32": scenario_sync(2, 32, 10, 0.01),
+        "async_w4_b64": scenario_async(1, 4, 64, 100, 0.01),
+        "outage_w8_b64": scenario_outage(8, 64, 20, 50, 0.01),
+        "versions_w64_b128": scenario_versions(64, 128, 8, 50, 0.01),
+        "outage_w256_b256": scenario_outage(256, 256, 0, 4, 0.005, DRAIN_SUM),
+    }

@@ -1,0 +1,282 @@
+"""HIP path vs CPU oracle, through the C ABI, on the same seeded inputs."""
+import os
+import sys
+import time
+
+import numpy as np
+import pytest
+
+from oracle import oracle as orc
+from oracle.sim import OracleReplay
+from paper_2406_05546_amd import synth
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+DATA_SEED = 11
+DROP_SEED = (0x5EED << 32) | 0x2406
+P_DROP = 0.25
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def ps():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2406_05546_amd import binding
+    binding.load_library()
+    return binding
+
+
+def _torch_inputs(x, y):
+    import torch
+    return torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda()
+
+
+# ------------------------------------------------------------------ one batched call in detail
+
+def test_one_call_decisions_gradients_and_stale_slots(ps):
+    """3 workers in a context sized for 4, two different snapshots, odd batch size."""
+    B, n = 37, 3
+    theta_a = synth.he_uniform_theta(5)
+    theta_b = synth.he_uniform_theta(6)
+    theta_b[synth.NetDims().segments()[1][1]:][:16] = 0.05          # non-zero biases in the second snapshot
+    theta_b[807616:807616 + 512] = np.linspace(-0.05, 0.05, 512, dtype=np.float32)
+    ctx = ps.ps_init(ps.make_config(4, B, 2, 6, DROP_SEED, P_DROP))
+    try:
+        # two-version ring: slot 0 = a, slot 1 = b (reached by one async update from a)
+        ps.ps_set_weights(ctx, theta_a)
+        g = ps.ps_queue_push_host(ctx, (theta_a - theta_b).astype(np.float32), 9, 0, 0)
+        ps.ps_apply_async(ctx, g, 1.0)                                # theta = a - (a - b) = b
+        ps.ps_snapshot_weights(ctx, 1)
+        got_b = ps.ps_get_weights(ctx, 1)
+        assert np.allclose(got_b, theta_b, rtol=0, atol=1e-6)
+        assert np.array_equal(ps.ps_get_weights(ctx, 0), theta_a)
+        workers, slots = [4, 2, 7], [0, 1, 1]
+        mbs = [synth.minibatch_id(w, 3) for w in workers]
+        x, y = synth.minibatches(DATA_SEED, mbs, B)
+        xd, yd = _torch_inputs(x, y)
+        import torch
+        loss = torch.zeros(n, device="cuda")
+        say("one_call: launching worker_grads_batched n=3 B=37")
+        entries = ps.worker_grads_batched(ctx, workers, slots, mbs, xd, yd, loss)
+        ps.ps_sync(ctx)
+        assert entries == [0, 1, 2]
+        meta = ps.ps_queue_meta(ctx)
+        assert [(m[0], m[1], m[2], m[3], m[4]) for m in meta] == \
+            [(1, 4, 0, mbs[0], 0), (2, 2, 1, mbs[1], 1), (3, 7, 1, mbs[2], 2)]
+        losses = loss.cpu().numpy()
+        near = 0
+        for i in range(n):
+            th = (theta_a if slots[i] == 0 else got_b).astype(np.float64)
+            keep = orc.dropout_keep(DROP_SEED, mbs[i], B, 512, P_DROP)
+            g_ref, l_ref, rec = orc.worker_grad(orc.Dims(), th, x[i], y[i], keep, P_DROP, records=True)
+            dbg = ps.ps_debug_last_batch(ctx, i)
+            near += parity.check_decisions(dbg, rec, keep, P_DROP, f"worker {i}")
+            errs = parity.assert_close(ps.ps_get_grad(ctx, entries[i]), g_ref, parity.GRAD_TOL, f"gradient {i}")
+            assert abs(losses[i] - l_ref) <= 1e-5 * abs(l_ref)
+            say(f"one_call: worker {i} grad rel err max {max(errs.values()):.2e}")
+        say(f"one_call: certified near-ties {near}")
+    finally:
+        ps.ps_destroy(ctx)
+
+
+def test_gradient_does_not_depend_on_batching(ps):
+    """The same logical minibatch gives the same bytes whether computed alone or next to others."""
+    B = 16
+    theta = synth.he_uniform_theta(2)
+    mbs = [synth.minibatch_id(w, 0) for w in range(5)]
+    x, y = synth.minibatches(DATA_SEED, mbs, B)
+    ctx = ps.ps_init(ps.make_config(5, B, 1, 6, DROP_SEED, P_DROP))
+    try:
+        ps.ps_set_weights(ctx, theta)
+        xd, yd = _torch_inputs(x, y)
+        e_all = ps.worker_grads_batched(ctx, range(5), [0] * 5, mbs, xd, yd)
+        xs, ys = _torch_inputs(x[3:4].copy(), y[3:4].copy())
+        e_one = ps.worker_grads_batched(ctx, [3], [0], mbs[3:4], xs, ys)
+        ps.ps_sync(ctx)
+        assert np.array_equal(ps.ps_get_grad(ctx, e_all[3]), ps.ps_get_grad(ctx, e_one[0]))
+        # and twice the same call gives the same bytes (fixed reduction order)
+        ps.ps_drain_buffered(ctx, ps.DRAIN_SUM, 0.0)
+        e_again = ps.worker_grads_batched(ctx, range(5), [0] * 5, mbs, xd, yd)
+        ps.ps_sync(ctx)
+        first = ps.ps_get_grad(ctx, e_again[0])
+        ps.ps_drain_buffered(ctx, ps.DRAIN_SUM, 0.0)
+        e_third = ps.worker_grads_batched(ctx, range(5), [0] * 5, mbs, xd, yd)
+        ps.ps_sync(ctx)
+        assert np.array_equal(first, ps.ps_get_grad(ctx, e_third[0]))
+    finally:
+        ps.ps_destroy(ctx)
+
+
+# ------------------------------------------------------------------ the evaluation configurations
+
+def _replay_both(ps, sc, check_every=1, n_threads=0):
+    from paper_2406_05546_amd.replay import Replay
+    theta0 = synth.he_uniform_theta(DATA_SEED)
+    t0 = time.time()
+    o = OracleReplay(sc, DATA_SEED, DROP_SEED, theta0, synth.minibatches, P_DROP, n_threads=n_threads)
+    theta_ref = o.run(keep_grads=lambda s: s % check_every == 0)
+    say(f"{sc.name}: oracle replay of {sc.n_gradients} gradients took {time.time() - t0:.1f} s "
+        f"({o.server.threads_used} threads)")
+    g = Replay(sc, DATA_SEED, DROP_SEED, theta0, P_DROP)
+    worst = {"grad": 0.0}
+
+    def on_grads(rp, seqs):
+        for s in seqs:
+            if s in o.grads:
+                errs = parity.assert_close(rp.grad(s), o.grads[s], parity.GRAD_TOL, f"{sc.name} gradient seq {s}")
+                worst["grad"] = max(worst["grad"], max(errs.values()))
+                assert abs(rp.losses[s] - o.losses[s]) <= 2e-5 * abs(o.losses[s])
+    try:
+        theta_gpu = g.run(on_grads)
+        assert g.meta_log == o.meta_log, f"{sc.name}: queue metadata / arrival order differs"
+        assert ps.ps_queue_meta(g.ctx) == [] and ps.ps_version(g.ctx) == o.server.version
+        errs = parity.assert_close(theta_gpu, theta_ref, parity.WEIGHT_TOL, f"{sc.name} final weights")
+        moved = np.linalg.norm(theta_ref - theta0) / np.linalg.norm(theta0)
+        say(f"{sc.name}: worst gradient rel err {worst['grad']:.2e}; weights rel err {max(errs.values()):.2e}; "
+            f"weights moved {moved:.2e}")
+        assert moved > 1e-4
+        # the difference from the oracle is far below the distance travelled
+        assert np.linalg.norm(theta_gpu - theta_ref) <= 1e-3 * np.linalg.norm(theta_ref - theta0)
+    finally:
+        g.close()
+
+
+def test_config_sync_w2_b32(ps):
+    _replay_both(ps, synth.paper_configs()["sync_w2_b32"])
+
+
+def test_config_async_w4_b64(ps):
+    _replay_both(ps, synth.paper_configs()["async_w4_b64"])
+
+
+def test_config_outage_w8_b64(ps):
+    _replay_both(ps, synth.paper_configs()["outage_w8_b64"], check_every=7)
+
+
+def test_config_versions_w64_b128_two_steps(ps):
+    """Eight resident versions, 64 workers per call; two of the 50 steps keep the oracle within seconds."""
+    _replay_both(ps, synth.scenario_versions(64, 128, 8, 2, 0.01), check_every=9)
+
+
+# ------------------------------------------------------------------ full-size checks
+
+def test_full_size_round_sampled_workers(ps):
+    """W=256, B=256 in one call (the launch configuration the bench times); the oracle checks a
+    sample of workers one by one."""
+    import torch
+    W, B = 256, 256
+    theta0 = synth.he_uniform_theta(DATA_SEED)
+    mbs = [synth.minibatch_id(w, 0) for w in range(W)]
+    x, y = synth.minibatches(DATA_SEED, mbs, B)
+    ctx = ps.ps_init(ps.make_config(W, B, 1, W, DROP_SEED, P_DROP))
+    try:
+        ps.ps_set_weights(ctx, theta0)
+        xd, yd = _torch_inputs(x, y)
+        loss = torch.zeros(W, device="cuda")
+        say("full_size: launching W=256 B=256")
+        entries = ps.worker_grads_batched(ctx, range(W), [0] * W, mbs, xd, yd, loss)
+        ps.ps_sync(ctx)
+        losses = loss.cpu().numpy()
+        assert np.isfinite(losses).all()
+        for w in (0, 101, 255):
+            keep = orc.dropout_keep(DROP_SEED, mbs[w], B, 512, P_DROP)
+            g_ref, l_ref, rec = orc.worker_grad(orc.Dims(), theta0.astype(np.float64), x[w], y[w], keep, P_DROP,
+                                                records=True)
+            errs = parity.assert_close(ps.ps_get_grad(ctx, entries[w]), g_ref, parity.GRAD_TOL, f"worker {w}")
+            parity.check_decisions(ps.ps_debug_last_batch(ctx, w), rec, keep, P_DROP, f"worker {w}")
+            assert abs(losses[w] - l_ref) <= 2e-5 * abs(l_ref)
+            say(f"full_size: worker {w} rel err {max(errs.values()):.2e}")
+    finally:
+        ps.ps_destroy(ctx)
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_full_size_drain_1024(ps, mode):
+    """1024 buffered gradients (3.3 GB) drained as one summed update and as 1024 successive updates.
+    Stand-in gradient rows keep the oracle's side to seconds."""
+    K, lr = 1024, 0.005
+    theta0 = synth.he_uniform_theta(3)
+    ctx = ps.ps_init(ps.make_config(1, 1, 1, K, DROP_SEED, P_DROP))
+    try:
+        ps.ps_set_weights(ctx, theta0)
+        ref = theta0.astype(np.float64)
+        total = np.zeros_like(ref)
+        for k0 in range(0, K, 64):
+            rows = synth.gradient_rows(17, k0, 64, ps.P)
+            for i in range(64):
+                assert ps.ps_queue_push_host(ctx, rows[i], (k0 + i) % 256, 0, k0 + i) == k0 + i
+            if mode == 0:
+                total += rows.astype(np.float64).sum(axis=0)
+            else:
+                for i in range(64):
+                    ref = orc.apply_async(ref, rows[i], lr)
+        if mode == 0:
+            ref = ref - lr * total
+        say(f"drain_1024: queue filled, draining mode {mode}")
+        assert ps.ps_drain_buffered(ctx, mode, lr) == K
+        got = ps.ps_get_weights(ctx)
+        assert ps.ps_drain_buffered(ctx, mode, lr) == 0 and ps.ps_version(ctx) == (1 if mode == 0 else K)
+        assert np.array_equal(ps.ps_get_weights(ctx), got)            # second drain is a no-op
+        parity.assert_close(got, ref, parity.WEIGHT_TOL, "drained weights")
+        moved = np.abs(ref - theta0).max()
+        assert np.abs(got - ref).max() <= 1e-3 * moved
+    finally:
+        ps.ps_destroy(ctx)
+
+
+# ------------------------------------------------------------------ edges and errors
+
+def test_edges_and_error_codes(ps):
+    import torch
+    B = 4
+    ctx = ps.ps_init(ps.make_config(2, B, 1, 3, DROP_SEED, 0.0))
+    try:
+        theta = synth.he_uniform_theta(1)
+        ps.ps_set_weights(ctx, theta)
+        assert ps.worker_grads_batched(ctx, [], [], [], None, None) == []            # empty call
+        assert ps.ps_drain_buffered(ctx, ps.DRAIN_SEQ, 0.1) == 0                      # empty drain
+        ps.ps_apply_sync(ctx, [], 0.1)
+        assert ps.ps_version(ctx) == 0 and np.array_equal(ps.ps_get_weights(ctx), theta)
+        mbs = [1, 2]
+        x, y = synth.minibatches(DATA_SEED, mbs, B)
+        xd, yd = _torch_inputs(x, y)
+        e = ps.worker_grads_batched(ctx, [0, 1], [0, 0], mbs, xd, yd)
+        ps.ps_sync(ctx)
+        # p = 0: nothing is dropped
+        dbg = ps.ps_debug_last_batch(ctx, 1)
+        assert dbg["keep"].all()
+        g_ref, _ = orc.worker_grad(orc.Dims(), theta.astype(np.float64), x[1], y[1], np.ones((B, 512), np.uint8), 0.0)
+        parity.assert_close(ps.ps_get_grad(ctx, e[1]), g_ref, parity.GRAD_TOL, "p=0 gradient")
+        for call, status in (
+            (lambda: ps.worker_grads_batched(ctx, [0, 1], [0, 0], mbs, xd, yd), ps.PS_EFULL),     # 1 entry left
+            (lambda: ps.worker_grads_batched(ctx, [0, 1, 2], [0] * 3, [1, 2, 3], xd, yd), ps.PS_EINVAL),
+            (lambda: ps.worker_grads_batched(ctx, [0], [1], [1], xd, yd), ps.PS_EINVAL),          # slot outside ring
+            (lambda: ps.ps_apply_async(ctx, 2, 0.1), ps.PS_ESTATE),                               # never written
+            (lambda: ps.ps_apply_async(ctx, 3, 0.1), ps.PS_EINVAL),
+            (lambda: ps.ps_apply_sync(ctx, [e[0], e[0]], 0.1), ps.PS_ESTATE),                     # listed twice
+            (lambda: ps.ps_get_grad(ctx, 2), ps.PS_ESTATE),
+            (lambda: ps.ps_snapshot_weights(ctx, 1), ps.PS_EINVAL),
+            (lambda: ps.ps_set_weights(ctx, theta), ps.PS_ESTATE),                                # queue not empty
+            (lambda: ps.ps_drain_buffered(ctx, 2, 0.1), ps.PS_EINVAL),
+        ):
+            with pytest.raises(ps.PsError) as err:
+                call()
+            assert err.value.status == status, str(err.value)
+        assert len(ps.ps_queue_meta(ctx)) == 2                                         # failed calls appended nothing
+        ps.ps_apply_async(ctx, e[0], 0.1)
+        with pytest.raises(ps.PsError) as err:
+            ps.ps_apply_async(ctx, e[0], 0.1)                                          # already applied
+        assert err.value.status == ps.PS_ESTATE
+        # a freed entry is handed out again, and the queue can be filled to capacity
+        e2 = ps.worker_grads_batched(ctx, [0, 1], [0, 0], [5, 6], xd, yd)
+        assert sorted(e2 + [e[1]]) == [0, 1, 2] and len(ps.ps_queue_meta(ctx)) == 3
+        assert [m[0] for m in ps.ps_queue_meta(ctx)] == [1, 2, 3]                      # arrival order kept
+        assert ps.ps_drain_buffered(ctx, ps.DRAIN_SUM, 0.1) == 3 and ps.ps_version(ctx) == 2
+    finally:
+        ps.ps_destroy(ctx)
