@@ -60,7 +60,7 @@ def _load():
                                             ctypes.c_uint32, ctypes.c_void_p]
         lib.oracle_worker_grad.restype = None
         lib.oracle_worker_grad.argtypes = [ctypes.POINTER(_Dims)] + [ctypes.c_void_p] * 3 + [ctypes.c_int32] + \
-            [ctypes.c_void_p, ctypes.c_double] + [ctypes.c_void_p] * 10
+            [ctypes.c_void_p, ctypes.c_double] + [ctypes.c_void_p] * 10 + [ctypes.c_void_p, ctypes.c_int32]
         lib.oracle_worker_grads.restype = ctypes.c_int32
         lib.oracle_worker_grads.argtypes = [ctypes.POINTER(_Dims), ctypes.c_int32] + [ctypes.c_void_p] * 4 + \
             [ctypes.c_int32, ctypes.c_void_p, ctypes.c_double, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32]
@@ -133,8 +133,10 @@ class Records:
 
 
 def worker_grad(dims: Dims, theta: np.ndarray, x: np.ndarray, y: np.ndarray, keep: np.ndarray, p: float,
-                records: bool = False):
-    """Gradient (fp64 [P]) of one worker's mean minibatch loss at `theta`; returns (grad, loss[, Records])."""
+                records: bool = False, forced: Optional[np.ndarray] = None):
+    """Gradient (fp64 [P]) of one worker's mean minibatch loss at `theta`; returns (grad, loss[, Records]).
+    `forced` (int32 [k, 4] rows {sample, layer, index, value}) makes tied max / ReLU decisions take a
+    stated outcome; see ps_oracle.c."""
     B = int(x.shape[0])
     theta = np.ascontiguousarray(theta, dtype=np.float64)
     x = np.ascontiguousarray(x, dtype=np.float64).reshape(B, dims.H * dims.W)
@@ -150,12 +152,15 @@ def worker_grad(dims: Dims, theta: np.ndarray, x: np.ndarray, y: np.ndarray, kee
                       np.empty((B, dims.n2), np.uint8), np.empty((B, dims.n2)), np.empty((B, dims.n2)),
                       np.empty((B, dims.F)), np.empty((B, dims.NC)))
     r = rec
+    if forced is not None:
+        forced = np.ascontiguousarray(forced, dtype=np.int32).reshape(-1, 4)
     _load().oracle_worker_grad(ctypes.byref(dims._c()), _ptr(theta), _ptr(x), _ptr(y), B, _ptr(keep),
                                ctypes.c_double(1.0 / (1.0 - p)), _ptr(grad), ctypes.byref(loss),
                                _ptr(r.code1) if r else None, _ptr(r.top1) if r else None,
                                _ptr(r.margin1) if r else None, _ptr(r.code2) if r else None,
                                _ptr(r.top2) if r else None, _ptr(r.margin2) if r else None,
-                               _ptr(r.hpre) if r else None, _ptr(r.z) if r else None)
+                               _ptr(r.hpre) if r else None, _ptr(r.z) if r else None,
+                               _ptr(forced), 0 if forced is None else len(forced))
     return (grad, loss.value, rec) if records else (grad, loss.value)
 
 

@@ -151,11 +151,16 @@ static void relu_pool2(int C, int H, int W, const double* pre, double* pooled, u
  *  loss  [1]        out, mean cross-entropy (natural log)
  * Optional per-sample records (NULL to skip), used for decision parity:
  *  code1/top1/margin1 [B][C1*(H/2)*(W/2)], code2/top2/margin2 [B][C2*(H/4)*(W/4)],
- *  hpre [B][F] fc1 pre-activation, z [B][NC] logits.                   */
+ *  hpre [B][F] fc1 pre-activation, z [B][NC] logits.
+ * Optional forced decisions: n_forced records of four int32 {sample, layer, index, value}.  A max
+ * or a ReLU whose arguments tie within rounding reach has two equally valid outcomes; a record
+ * makes this pass take the stated one: layer 1 / 2 = pooled output `index` of pool1 / pool2 takes
+ * window element (value & 3) as its winner and lets gradient through iff (value >> 2) & 1;
+ * layer 3 = fc1 unit `index` lets gradient through iff value != 0.            */
 void oracle_worker_grad(const oracle_dims* d, const double* theta, const double* x, const int32_t* y, int32_t B,
                         const uint8_t* keep, double scale, double* grad, double* loss, uint8_t* code1,
                         double* top1, double* margin1, uint8_t* code2, double* top2, double* margin2,
-                        double* hpre_out, double* z_out)
+                        double* hpre_out, double* z_out, const int32_t* forced, int32_t n_forced)
 {
     const int H = d->H, W = d->W, C1 = d->C1, C2 = d->C2, F = d->F, NC = d->NC;
     const int H1 = H / 2, W1 = W / 2, H2 = H / 4, W2 = W / 4;
@@ -200,6 +205,9 @@ void oracle_worker_grad(const oracle_dims* d, const double* theta, const double*
     double* dc2 = malloc(sizeof(double) * (size_t)C2 * H1 * W1);
     double* dp1 = malloc(sizeof(double) * (size_t)n1);
     double* dc1 = malloc(sizeof(double) * (size_t)C1 * H * W);
+    uint8_t* g1 = malloc((size_t)n1); /* gradient passes the ReLU under the pool */
+    uint8_t* g2 = malloc((size_t)n2);
+    uint8_t* g3 = malloc((size_t)F);
 
     double loss_sum = 0.0;
     for (int s = 0; s < B; ++s) {
@@ -209,14 +217,39 @@ void oracle_worker_grad(const oracle_dims* d, const double* theta, const double*
         /* ---- forward ---- */
         conv3x3(1, C1, H, W, xs, Wc1, bc1, c1);
         relu_pool2(C1, H, W, c1, p1, k1, t1, m1);
+        for (int i = 0; i < n1; ++i) g1[i] = t1[i] > 0.0;
+        for (int r = 0; r < n_forced; ++r) {
+            const int32_t* f = forced + 4 * r;
+            if (f[0] != s || f[1] != 1) continue;
+            int idx = f[2], o = idx / (H1 * W1), py = (idx / W1) % H1, px = idx % W1, k = f[3] & 3;
+            double v = c1[(o * H + 2 * py + k / 2) * W + 2 * px + k % 2];
+            k1[idx] = (uint8_t)k;
+            g1[idx] = (uint8_t)((f[3] >> 2) & 1);
+            p1[idx] = v > 0.0 ? v : 0.0;
+        }
         conv3x3(C1, C2, H1, W1, p1, Wc2, bc2, c2);
         relu_pool2(C2, H1, W1, c2, p2, k2, t2, m2);
+        for (int i = 0; i < n2; ++i) g2[i] = t2[i] > 0.0;
+        for (int r = 0; r < n_forced; ++r) {
+            const int32_t* f = forced + 4 * r;
+            if (f[0] != s || f[1] != 2) continue;
+            int idx = f[2], o = idx / (H2 * W2), py = (idx / W2) % H2, px = idx % W2, k = f[3] & 3;
+            double v = c2[(o * H1 + 2 * py + k / 2) * W1 + 2 * px + k % 2];
+            k2[idx] = (uint8_t)k;
+            g2[idx] = (uint8_t)((f[3] >> 2) & 1);
+            p2[idx] = v > 0.0 ? v : 0.0;
+        }
         for (int u = 0; u < F; ++u) {
             double acc = bf1[u];
             for (int i = 0; i < n2; ++i) acc += Wf1[(int64_t)u * n2 + i] * p2[i];
             hpre[u] = acc;
+            g3[u] = acc > 0.0;
             double r = acc > 0.0 ? acc : 0.0;
             hd[u] = ks[u] ? r * scale : 0.0;
+        }
+        for (int r = 0; r < n_forced; ++r) {
+            const int32_t* f = forced + 4 * r;
+            if (f[0] == s && f[1] == 3) g3[f[2]] = f[3] != 0;
         }
         double zmax = -INFINITY;
         for (int j = 0; j < NC; ++j) {
@@ -249,7 +282,7 @@ void oracle_worker_grad(const oracle_dims* d, const double* theta, const double*
             double acc = 0.0;
             for (int j = 0; j < NC; ++j) acc += dz[j] * Wf2[(int64_t)j * F + u];
             /* through dropout (same mask and scale), then through ReLU (derivative 0 at 0) */
-            dh[u] = (ks[u] && hpre[u] > 0.0) ? acc * scale : 0.0;
+            dh[u] = (ks[u] && g3[u]) ? acc * scale : 0.0;
         }
         for (int u = 0; u < F; ++u) {
             gbf1[u] += dh[u];
@@ -266,7 +299,7 @@ void oracle_worker_grad(const oracle_dims* d, const double* theta, const double*
             for (int py = 0; py < H2; ++py)
                 for (int px = 0; px < W2; ++px) {
                     int idx = (o * H2 + py) * W2 + px;
-                    if (t2[idx] > 0.0)
+                    if (g2[idx])
                         dc2[(o * H1 + 2 * py + k2[idx] / 2) * W1 + 2 * px + k2[idx] % 2] = dp2[idx];
                 }
         memset(dp1, 0, sizeof(double) * (size_t)n1);
@@ -291,7 +324,7 @@ void oracle_worker_grad(const oracle_dims* d, const double* theta, const double*
             for (int py = 0; py < H1; ++py)
                 for (int px = 0; px < W1; ++px) {
                     int idx = (o * H1 + py) * W1 + px;
-                    if (t1[idx] > 0.0) dc1[(o * H + 2 * py + k1[idx] / 2) * W + 2 * px + k1[idx] % 2] = dp1[idx];
+                    if (g1[idx]) dc1[(o * H + 2 * py + k1[idx] / 2) * W + 2 * px + k1[idx] % 2] = dp1[idx];
                 }
         for (int o = 0; o < C1; ++o)
             for (int yy = 0; yy < H; ++yy)
@@ -310,7 +343,7 @@ void oracle_worker_grad(const oracle_dims* d, const double* theta, const double*
     *loss = loss_sum / (double)B;
 
     free(c1); free(p1); free(c2); free(p2); free(k1); free(k2); free(t1); free(m1); free(t2); free(m2);
-    free(hpre); free(hd); free(z); free(dz); free(dh); free(dp2); free(dc2); free(dp1); free(dc1);
+    free(hpre); free(hd); free(z); free(dz); free(dh); free(dp2); free(dc2); free(dp1); free(dc1); free(g1); free(g2); free(g3);
 }
 
 /* n independent workers, each with its own snapshot, minibatch and mask
@@ -333,6 +366,6 @@ int32_t oracle_worker_grads(const oracle_dims* d, int32_t n, const double* theta
     for (int32_t w = 0; w < n; ++w)
         oracle_worker_grad(d, thetas + (int64_t)theta_of[w] * P, x + (int64_t)w * B * HW, y + (int64_t)w * B, B,
                            keep + (int64_t)w * B * d->F, scale, grads + (int64_t)w * P, losses + w, NULL, NULL,
-                           NULL, NULL, NULL, NULL, NULL, NULL);
+                           NULL, NULL, NULL, NULL, NULL, NULL, NULL, 0);
     return used;
 }

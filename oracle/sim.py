@@ -2,7 +2,7 @@
 TEST INFRASTRUCTURE ONLY; never imported by the product path."""
 from __future__ import annotations
 
-from typing import Callable, Dict, List, Optional
+from typing import Callable, Dict, Iterator, List, Tuple
 
 import numpy as np
 
@@ -19,21 +19,23 @@ class OracleReplay:
         self.server = orc.OracleServer(dims, seed=dropout_seed, dropout_p=dropout_p, n_slots=scenario.n_slots,
                                        theta=theta0, n_threads=n_threads)
         self.meta_log: List[tuple] = []
-        self.grads: Dict[int, np.ndarray] = {}
+        self.last: Dict[int, orc.QueueEntry] = {}     # entries appended by the most recent "grads" event
         self.losses: Dict[int, float] = {}
 
-    def run(self, keep_grads: Optional[Callable[[int], bool]] = None) -> np.ndarray:
+    def steps(self) -> Iterator[Tuple[tuple, List[int]]]:
+        """Executes the events one by one; yields (event, arrival numbers it appended) after each."""
         sv = self.server
         for ev in self.sc.events:
-            kind = ev[0]
+            kind, seqs = ev[0], []
             if kind == "grads":
                 _, workers, slots, mbs = ev
                 x, y = self.minibatches(self.data_seed, mbs, self.sc.batch)
+                self.last = {}
                 for e in sv.worker_grads_batched(workers, slots, mbs, x, y):
                     self.meta_log.append((e.seq, e.worker, e.version, e.mb_id))
                     self.losses[e.seq] = e.loss
-                    if keep_grads is None or keep_grads(e.seq):
-                        self.grads[e.seq] = e.grad
+                    self.last[e.seq] = e
+                    seqs.append(e.seq)
             elif kind == "sync":
                 sv.apply_sync(ev[1], ev[2])
             elif kind == "async":
@@ -44,4 +46,9 @@ class OracleReplay:
                 sv.snapshot_weights(ev[1])
             else:
                 raise ValueError(kind)
-        return sv.theta
+            yield ev, seqs
+
+    def run(self) -> np.ndarray:
+        for _ in self.steps():
+            pass
+        return self.server.theta

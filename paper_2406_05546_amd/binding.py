@@ -179,7 +179,7 @@ def worker_grads_batched(ctx: Context, worker_id: Sequence[int], version_slot: S
         B = ctx.cfg.batch
         assert x_dev.is_cuda and x_dev.dtype == torch.float32 and x_dev.is_contiguous()
         assert y_dev.is_cuda and y_dev.dtype == torch.int32 and y_dev.is_contiguous()
-        assert x_dev.numel() == n * B * IMAGE_PIXELS and y_dev.numel() == n * B
+        assert x_dev.numel() >= n * B * IMAGE_PIXELS and y_dev.numel() >= n * B
         assert loss_dev is None or (loss_dev.is_cuda and loss_dev.dtype == torch.float32 and loss_dev.numel() >= n)
     q = np.full(n, -1, dtype=np.int32)
     st = load_library().worker_grads_batched(

@@ -1,7 +1,7 @@
 """Replays a synth.Scenario through the C ABI (host-side sequencing only)."""
 from __future__ import annotations
 
-from typing import Callable, Dict, List, Optional
+from typing import Dict, Iterator, List, Tuple
 
 import numpy as np
 
@@ -30,10 +30,11 @@ class Replay:
     def close(self):
         ps.ps_destroy(self.ctx)
 
-    def run(self, on_grads: Optional[Callable[["Replay", List[int]], None]] = None) -> np.ndarray:
+    def steps(self) -> Iterator[Tuple[tuple, List[int]]]:
+        """Executes the events one by one; yields (event, arrival numbers it appended) after each."""
         torch = self.torch
         for ev in self.sc.events:
-            kind = ev[0]
+            kind, seqs = ev[0], []
             if kind == "grads":
                 _, workers, slots, mbs = ev
                 x, y = synth.minibatches(self.data_seed, mbs, self.sc.batch)
@@ -43,17 +44,14 @@ class Replay:
                 entries = ps.worker_grads_batched(self.ctx, workers, slots, mbs, xd, yd, loss)
                 seqs = list(range(self.next_seq, self.next_seq + len(workers)))
                 self.next_seq += len(workers)
-                for s, q in zip(seqs, entries):
-                    self.entry_of[s] = q
                 by_entry = {m[4]: m for m in ps.ps_queue_meta(self.ctx)}
                 for s, q in zip(seqs, entries):
+                    self.entry_of[s] = q
                     m = by_entry[q]
                     self.meta_log.append((m[0], m[1], m[2], m[3]))
                 ps.ps_sync(self.ctx)                      # x, y, loss are borrowed until the work is done
                 for s, l in zip(seqs, loss.cpu().numpy()):
                     self.losses[s] = float(l)
-                if on_grads is not None:
-                    on_grads(self, seqs)
             elif kind == "sync":
                 ps.ps_apply_sync(self.ctx, [self.entry_of.pop(s) for s in ev[1]], ev[2])
             elif kind == "async":
@@ -66,6 +64,14 @@ class Replay:
                 ps.ps_snapshot_weights(self.ctx, ev[1])
             else:
                 raise ValueError(kind)
+            yield ev, seqs
+
+    def run(self) -> np.ndarray:
+        for _ in self.steps():
+            pass
+        return self.weights()
+
+    def weights(self) -> np.ndarray:
         return ps.ps_get_weights(self.ctx)
 
     def grad(self, seq: int) -> np.ndarray:

@@ -2,12 +2,19 @@
 
 Floating point: per tensor, ||gpu - oracle||_2 <= tol * ||oracle||_2 with tol = 1e-4 for gradients
 and 1e-3 for weights after the configured number of steps.
-Decisions (pool winners, ReLU gates, predicted class): bit-exact wherever the oracle's own margin
-exceeds the fp32 rounding reach of the decision; the remaining near-ties are counted and bounded.
+
 Dropout keep masks and queue metadata: bit-exact, no exceptions.
+
+Decisions (pool winners, ReLU gates, predicted class): bit-exact wherever the oracle's own margin
+exceeds the fp32 rounding reach of the decision.  Inside that reach a max or a ReLU has two equally
+valid outcomes, and which one is taken changes a worker's conv gradients by far more than 1e-4 (one
+routed element among B*1568).  There the HIP path's choice is first checked to be one of the valid
+ones, and the oracle is then evaluated with that choice forced; every value still comes from the
+oracle's own arithmetic on the harness's inputs.
 """
 import numpy as np
 
+from oracle import oracle as orc
 from paper_2406_05546_amd import synth
 
 GRAD_TOL = 1e-4
@@ -27,6 +34,10 @@ def rel_errors(gpu: np.ndarray, ref: np.ndarray) -> dict:
     return out
 
 
+def is_close(gpu: np.ndarray, ref: np.ndarray, tol: float) -> bool:
+    return bool(np.isfinite(gpu).all()) and all(v <= tol for v in rel_errors(gpu, ref).values())
+
+
 def assert_close(gpu: np.ndarray, ref: np.ndarray, tol: float, what: str) -> dict:
     assert np.isfinite(gpu).all(), what
     errs = rel_errors(gpu, ref)
@@ -35,32 +46,53 @@ def assert_close(gpu: np.ndarray, ref: np.ndarray, tol: float, what: str) -> dic
     return errs
 
 
-def check_pool(gpu_bytes: np.ndarray, code: np.ndarray, top: np.ndarray, margin: np.ndarray, what: str) -> int:
-    """gpu_bytes: bits 0-1 winner, bit 2 gate.  Returns the number of certified near-ties."""
+def _pool_forced(layer, gpu_bytes, code, top, margin, tie_tol, what):
+    """Checks one pooling layer's decisions; returns forced records for valid departures."""
     scale = np.maximum(1.0, np.abs(top))
-    code_free = margin <= TIE_TOL * scale
-    gate_free = np.abs(top) <= TIE_TOL
-    code_bad = ((gpu_bytes & 3) != code) & ~code_free
-    gate_bad = (((gpu_bytes >> 2) & 1) != (top > 0)) & ~gate_free
-    assert not code_bad.any(), f"{what}: {int(code_bad.sum())} pool winners differ away from ties"
-    assert not gate_bad.any(), f"{what}: {int(gate_bad.sum())} ReLU gates differ away from zero"
+    code_free = margin <= tie_tol * scale
+    gate_free = np.abs(top) <= tie_tol
+    gpu_code, gpu_gate = gpu_bytes & 3, (gpu_bytes >> 2) & 1
+    code_diff, gate_diff = gpu_code != code, gpu_gate != (top > 0)
+    assert not (code_diff & ~code_free).any(), f"{what}: {int((code_diff & ~code_free).sum())} pool winners differ away from ties"
+    assert not (gate_diff & ~gate_free).any(), f"{what}: {int((gate_diff & ~gate_free).sum())} ReLU gates differ away from zero"
     assert (gpu_bytes >> 3 == 0).all(), what
     n_free = int(code_free.sum() + gate_free.sum())
-    assert n_free <= max(8, 2e-3 * code.size), f"{what}: implausibly many near-ties ({n_free})"
-    return n_free
+    assert n_free <= max(16, 4e-3 * code.size * tie_tol / 3e-5), f"{what}: implausibly many near-ties ({n_free})"
+    s, i = np.nonzero(code_diff | gate_diff)
+    return [[int(a), layer, int(b), int(gpu_bytes[a, b])] for a, b in zip(s, i)], n_free
 
 
-def check_decisions(dbg: dict, rec, keep: np.ndarray, p: float, what: str) -> int:
-    """dbg: ps_debug_last_batch output for one worker; rec: the oracle's Records; keep: oracle mask."""
+def decisions(dbg: dict, rec, keep: np.ndarray, p: float, what: str, tie_tol: float = TIE_TOL):
+    """dbg: ps_debug_last_batch output for one worker; rec: the oracle's Records; keep: oracle mask.
+    Asserts the bit-exact parts, returns (forced records for valid tie departures, near-tie count)."""
     assert np.array_equal(dbg["keep"], keep), f"{what}: dropout keep mask differs"
-    n_free = check_pool(dbg["pool1"], rec.code1, rec.top1, rec.margin1, what + " pool1")
-    n_free += check_pool(dbg["pool2"], rec.code2, rec.top2, rec.margin2, what + " pool2")
+    f1, n1 = _pool_forced(1, dbg["pool1"], rec.code1, rec.top1, rec.margin1, tie_tol, what + " pool1")
+    f2, n2 = _pool_forced(2, dbg["pool2"], rec.code2, rec.top2, rec.margin2, tie_tol, what + " pool2")
     # the mask the forward pass really used: dropped units are exactly zero, kept ones follow fc1
     h_ref = np.maximum(rec.hpre, 0.0) * keep / (1.0 - p)
     assert (dbg["hdrop"][keep == 0] == 0).all(), f"{what}: a dropped unit is not zero"
     assert np.allclose(dbg["hdrop"], h_ref, rtol=1e-4, atol=1e-4), f"{what}: fc1 activation"
+    kept = keep == 1
+    gate_diff = kept & ((dbg["hdrop"] > 0) != (rec.hpre > 0))
+    assert not (gate_diff & (np.abs(rec.hpre) > tie_tol)).any(), f"{what}: fc1 ReLU gates differ away from zero"
+    s, u = np.nonzero(gate_diff)
+    f3 = [[int(a), 3, int(b), int(dbg["hdrop"][a, b] > 0)] for a, b in zip(s, u)]
     assert np.allclose(dbg["z"], rec.z, rtol=1e-4, atol=1e-4), f"{what}: logits"
     zs = np.sort(rec.z, axis=1)
     clear = (zs[:, -1] - zs[:, -2]) > 1e-4
     assert np.array_equal(dbg["pred"][clear], rec.z.argmax(1)[clear]), f"{what}: predicted class"
-    return n_free
+    return np.array(f1 + f2 + f3, np.int32).reshape(-1, 4), n1 + n2
+
+
+def check_worker(ps, ctx, i: int, entry: int, theta: np.ndarray, x: np.ndarray, y: np.ndarray, mb_id: int,
+                 drop_seed: int, p: float, what: str, tie_tol: float = TIE_TOL) -> dict:
+    """Full parity of worker i of the last batched call: masks, decisions, gradient.
+    theta is the oracle's snapshot for that worker (fp64)."""
+    B = x.shape[0]
+    keep = orc.dropout_keep(drop_seed, mb_id, B, 512, p)
+    g_ref, l_ref, rec = orc.worker_grad(orc.Dims(), theta, x, y, keep, p, records=True)
+    forced, n_free = decisions(ps.ps_debug_last_batch(ctx, i), rec, keep, p, what, tie_tol)
+    if len(forced):
+        g_ref, l_ref = orc.worker_grad(orc.Dims(), theta, x, y, keep, p, forced=forced)
+    errs = assert_close(ps.ps_get_grad(ctx, entry), g_ref, GRAD_TOL, what)
+    return {"worst": max(errs.values()), "near_ties": n_free, "forced": len(forced), "loss": l_ref, "grad": g_ref}

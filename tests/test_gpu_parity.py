@@ -70,17 +70,11 @@ def test_one_call_decisions_gradients_and_stale_slots(ps):
         assert [(m[0], m[1], m[2], m[3], m[4]) for m in meta] == \
             [(1, 4, 0, mbs[0], 0), (2, 2, 1, mbs[1], 1), (3, 7, 1, mbs[2], 2)]
         losses = loss.cpu().numpy()
-        near = 0
         for i in range(n):
             th = (theta_a if slots[i] == 0 else got_b).astype(np.float64)
-            keep = orc.dropout_keep(DROP_SEED, mbs[i], B, 512, P_DROP)
-            g_ref, l_ref, rec = orc.worker_grad(orc.Dims(), th, x[i], y[i], keep, P_DROP, records=True)
-            dbg = ps.ps_debug_last_batch(ctx, i)
-            near += parity.check_decisions(dbg, rec, keep, P_DROP, f"worker {i}")
-            errs = parity.assert_close(ps.ps_get_grad(ctx, entries[i]), g_ref, parity.GRAD_TOL, f"gradient {i}")
-            assert abs(losses[i] - l_ref) <= 1e-5 * abs(l_ref)
-            say(f"one_call: worker {i} grad rel err max {max(errs.values()):.2e}")
-        say(f"one_call: certified near-ties {near}")
+            r = parity.check_worker(ps, ctx, i, entries[i], th, x[i], y[i], mbs[i], DROP_SEED, P_DROP, f"worker {i}")
+            assert abs(losses[i] - r["loss"]) <= 1e-5 * abs(r["loss"])
+            say(f"one_call: worker {i} grad rel err max {r['worst']:.2e}, near-ties {r['near_ties']}, forced {r['forced']}")
     finally:
         ps.ps_destroy(ctx)
 
@@ -115,34 +109,54 @@ def test_gradient_does_not_depend_on_batching(ps):
 
 # ------------------------------------------------------------------ the evaluation configurations
 
-def _replay_both(ps, sc, check_every=1, n_threads=0):
+def _replay_both(ps, sc, check_every=1, n_threads=0, tie_tol=1e-4):
+    """Both sides replay the scenario event by event; after every worker step the gradients are
+    compared (every `check_every`-th arrival), at the end the weights and the queue metadata."""
     from paper_2406_05546_amd.replay import Replay
     theta0 = synth.he_uniform_theta(DATA_SEED)
-    t0 = time.time()
     o = OracleReplay(sc, DATA_SEED, DROP_SEED, theta0, synth.minibatches, P_DROP, n_threads=n_threads)
-    theta_ref = o.run(keep_grads=lambda s: s % check_every == 0)
-    say(f"{sc.name}: oracle replay of {sc.n_gradients} gradients took {time.time() - t0:.1f} s "
-        f"({o.server.threads_used} threads)")
     g = Replay(sc, DATA_SEED, DROP_SEED, theta0, P_DROP)
-    worst = {"grad": 0.0}
-
-    def on_grads(rp, seqs):
-        for s in seqs:
-            if s in o.grads:
-                errs = parity.assert_close(rp.grad(s), o.grads[s], parity.GRAD_TOL, f"{sc.name} gradient seq {s}")
-                worst["grad"] = max(worst["grad"], max(errs.values()))
-                assert abs(rp.losses[s] - o.losses[s]) <= 2e-5 * abs(o.losses[s])
+    stats = {"worst": 0.0, "checked": 0, "tie_workers": 0, "forced": 0}
+    t0 = time.time()
     try:
-        theta_gpu = g.run(on_grads)
+        for (ev, seqs), (ev_o, seqs_o) in zip(g.steps(), o.steps()):
+            assert ev is ev_o and seqs == seqs_o
+            if ev[0] != "grads":
+                continue
+            _, workers, slots, mbs = ev
+            for i, s in enumerate(seqs):
+                if s % check_every:
+                    continue
+                stats["checked"] += 1
+                got = g.grad(s)
+                if parity.is_close(got, o.last[s].grad, parity.GRAD_TOL):
+                    stats["worst"] = max(stats["worst"], max(parity.rel_errors(got, o.last[s].grad).values()))
+                else:
+                    # some max / ReLU sat within rounding reach of a tie: check that the HIP path's
+                    # choice is a valid one and compare against the oracle under that choice
+                    x, y = synth.minibatch(DATA_SEED, mbs[i], sc.batch)
+                    r = parity.check_worker(ps, g.ctx, i, g.entry_of[s], o.server.ring[slots[i]], x, y, mbs[i],
+                                            DROP_SEED, P_DROP, f"{sc.name} gradient seq {s}", tie_tol)
+                    assert r["forced"] > 0, f"{sc.name} gradient seq {s} differs without any tie"
+                    stats["worst"] = max(stats["worst"], r["worst"])
+                    stats["tie_workers"] += 1
+                    stats["forced"] += r["forced"]
+                    # both outcomes of a tie are valid; the oracle's run continues on the branch taken
+                    # so that later steps stay comparable (values are still the oracle's own)
+                    o.last[s].grad[:] = r["grad"]
+                assert abs(g.losses[s] - o.losses[s]) <= 2e-5 * abs(o.losses[s])
+        theta_gpu, theta_ref = g.weights(), o.server.theta
         assert g.meta_log == o.meta_log, f"{sc.name}: queue metadata / arrival order differs"
         assert ps.ps_queue_meta(g.ctx) == [] and ps.ps_version(g.ctx) == o.server.version
         errs = parity.assert_close(theta_gpu, theta_ref, parity.WEIGHT_TOL, f"{sc.name} final weights")
         moved = np.linalg.norm(theta_ref - theta0) / np.linalg.norm(theta0)
-        say(f"{sc.name}: worst gradient rel err {worst['grad']:.2e}; weights rel err {max(errs.values()):.2e}; "
-            f"weights moved {moved:.2e}")
-        assert moved > 1e-4
+        say(f"{sc.name}: {sc.n_gradients} gradients, {stats['checked']} checked, worst rel err {stats['worst']:.2e}, "
+            f"{stats['tie_workers']} with tie departures ({stats['forced']} decisions); weights rel err "
+            f"{max(errs.values()):.2e}; weights moved {moved:.2e}; {time.time() - t0:.1f} s, "
+            f"{o.server.threads_used} oracle threads")
+        assert moved > 1e-4 and stats["tie_workers"] <= max(2, stats["checked"] // 4)
         # the difference from the oracle is far below the distance travelled
-        assert np.linalg.norm(theta_gpu - theta_ref) <= 1e-3 * np.linalg.norm(theta_ref - theta0)
+        assert np.linalg.norm(theta_gpu - theta_ref) <= 2e-3 * np.linalg.norm(theta_ref - theta0)
     finally:
         g.close()
 
@@ -156,12 +170,12 @@ def test_config_async_w4_b64(ps):
 
 
 def test_config_outage_w8_b64(ps):
-    _replay_both(ps, synth.paper_configs()["outage_w8_b64"], check_every=7)
+    _replay_both(ps, synth.paper_configs()["outage_w8_b64"])
 
 
 def test_config_versions_w64_b128_two_steps(ps):
     """Eight resident versions, 64 workers per call; two of the 50 steps keep the oracle within seconds."""
-    _replay_both(ps, synth.scenario_versions(64, 128, 8, 2, 0.01), check_every=9)
+    _replay_both(ps, synth.scenario_versions(64, 128, 8, 2, 0.01))
 
 
 # ------------------------------------------------------------------ full-size checks
@@ -185,13 +199,10 @@ def test_full_size_round_sampled_workers(ps):
         losses = loss.cpu().numpy()
         assert np.isfinite(losses).all()
         for w in (0, 101, 255):
-            keep = orc.dropout_keep(DROP_SEED, mbs[w], B, 512, P_DROP)
-            g_ref, l_ref, rec = orc.worker_grad(orc.Dims(), theta0.astype(np.float64), x[w], y[w], keep, P_DROP,
-                                                records=True)
-            errs = parity.assert_close(ps.ps_get_grad(ctx, entries[w]), g_ref, parity.GRAD_TOL, f"worker {w}")
-            parity.check_decisions(ps.ps_debug_last_batch(ctx, w), rec, keep, P_DROP, f"worker {w}")
-            assert abs(losses[w] - l_ref) <= 2e-5 * abs(l_ref)
-            say(f"full_size: worker {w} rel err {max(errs.values()):.2e}")
+            r = parity.check_worker(ps, ctx, w, entries[w], theta0.astype(np.float64), x[w], y[w], mbs[w], DROP_SEED,
+                                    P_DROP, f"worker {w}")
+            assert abs(losses[w] - r["loss"]) <= 2e-5 * abs(r["loss"])
+            say(f"full_size: worker {w} rel err {r['worst']:.2e}, near-ties {r['near_ties']}, forced {r['forced']}")
     finally:
         ps.ps_destroy(ctx)
 
@@ -244,15 +255,13 @@ def test_edges_and_error_codes(ps):
         ps.ps_apply_sync(ctx, [], 0.1)
         assert ps.ps_version(ctx) == 0 and np.array_equal(ps.ps_get_weights(ctx), theta)
         mbs = [1, 2]
-        x, y = synth.minibatches(DATA_SEED, mbs, B)
+        x, y = synth.minibatches(DATA_SEED, mbs + [3], B)               # room for a third worker's data
         xd, yd = _torch_inputs(x, y)
         e = ps.worker_grads_batched(ctx, [0, 1], [0, 0], mbs, xd, yd)
         ps.ps_sync(ctx)
         # p = 0: nothing is dropped
-        dbg = ps.ps_debug_last_batch(ctx, 1)
-        assert dbg["keep"].all()
-        g_ref, _ = orc.worker_grad(orc.Dims(), theta.astype(np.float64), x[1], y[1], np.ones((B, 512), np.uint8), 0.0)
-        parity.assert_close(ps.ps_get_grad(ctx, e[1]), g_ref, parity.GRAD_TOL, "p=0 gradient")
+        assert ps.ps_debug_last_batch(ctx, 1)["keep"].all()
+        parity.check_worker(ps, ctx, 1, e[1], theta.astype(np.float64), x[1], y[1], mbs[1], DROP_SEED, 0.0, "p=0")
         for call, status in (
             (lambda: ps.worker_grads_batched(ctx, [0, 1], [0, 0], mbs, xd, yd), ps.PS_EFULL),     # 1 entry left
             (lambda: ps.worker_grads_batched(ctx, [0, 1, 2], [0] * 3, [1, 2, 3], xd, yd), ps.PS_EINVAL),

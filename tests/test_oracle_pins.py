@@ -345,3 +345,69 @@ def test_update_direction_first_order():
     for new in (orc.apply_async(theta, g, lr), orc.apply_sync(theta, [g], lr), orc.drain(theta, [g], lr, orc.DRAIN_SEQ)):
         l1 = orc.worker_grad(d, new, x, y, keep, 0.25)[1]
         assert abs((l0 - l1) / (lr * g.dot(g)) - 1.0) < 1e-3
+
+
+# ---------------------------------------------------------------- forced tie decisions
+
+def test_forcing_the_oracles_own_decisions_changes_nothing():
+    d, B = TINY, 3
+    x, y = _rand_batch(d, B, 31)
+    theta = _rand_theta(d, 32)
+    keep = orc.dropout_keep(1, 1, B, d.F, 0.25)
+    g, loss, rec = orc.worker_grad(d, theta, x, y, keep, 0.25, records=True)
+    forced = []
+    for s in range(B):
+        forced += [[s, 1, i, int(rec.code1[s, i]) | (4 if rec.top1[s, i] > 0 else 0)] for i in range(d.n1)]
+        forced += [[s, 2, i, int(rec.code2[s, i]) | (4 if rec.top2[s, i] > 0 else 0)] for i in range(d.n2)]
+        forced += [[s, 3, u, int(rec.hpre[s, u] > 0)] for u in range(d.F)]
+    g2, loss2 = orc.worker_grad(d, theta, x, y, keep, 0.25, forced=np.array(forced, np.int32))
+    assert np.array_equal(g, g2) and loss == loss2
+
+
+def test_forced_decision_equals_the_natural_one_across_a_tie():
+    """Nudging an input across a tie by 1e-12 flips the natural decision; forcing that decision on the
+    un-nudged side must give the same gradient up to the size of the nudge."""
+    d, B = orc.Dims(H=8, W=8, C1=2, C2=3, F=8, NC=3), 2
+    theta = _rand_theta(d, 40)
+    theta[0:18] = 0.0
+    theta[4] = 1.0          # conv1 channel 0 = identity on the image
+    theta[9 + 4] = 0.7      # conv1 channel 1 = 0.7 * image
+    theta[18:20] = 0.0
+    x, y = _rand_batch(d, B, 41)
+    keep = np.ones((B, d.F), np.uint8)
+    # pool1 winner tie: window (0,0) of sample 1, elements 1 and 2 are the two largest and nearly equal
+    xa = x.copy().reshape(B, 8, 8)
+    xa[1, 0, 0], xa[1, 1, 1] = 0.1, 0.2
+    xa[1, 0, 1], xa[1, 1, 0] = 0.9 + 1e-12, 0.9
+    xb = xa.copy()
+    xb[1, 0, 1], xb[1, 1, 0] = 0.9, 0.9 + 1e-12
+    ga, _, ra = orc.worker_grad(d, theta, xa.reshape(B, 64), y, keep, 0.0, records=True)
+    gb, _, rb = orc.worker_grad(d, theta, xb.reshape(B, 64), y, keep, 0.0, records=True)
+    assert ra.code1[1, 0] == 1 and rb.code1[1, 0] == 2 and ra.margin1[1, 0] < 1e-11
+    assert np.linalg.norm(ga - gb) > 1e-6 * np.linalg.norm(ga)          # the choice matters
+    forced = np.array([[1, 1, 0, 2 | 4], [1, 1, 16, 2 | 4]], np.int32)   # both channels see the same window
+    gf, _ = orc.worker_grad(d, theta, xa.reshape(B, 64), y, keep, 0.0, forced=forced)
+    assert np.linalg.norm(gf - gb) <= 1e-9 * np.linalg.norm(gb)
+    # fc1 ReLU gate: put unit 3 of sample 0 a hair above / below zero through its bias
+    off_b = d.C1 * 10 + d.C2 * d.C1 * 9 + d.C2 + d.F * d.n2
+    _, _, r0 = orc.worker_grad(d, theta, x, y, keep, 0.0, records=True)
+    tp, tm = theta.copy(), theta.copy()
+    tp[off_b + 3] += -r0.hpre[0, 3] + 1e-12
+    tm[off_b + 3] += -r0.hpre[0, 3] - 1e-12
+    gp, _, rp = orc.worker_grad(d, tp, x, y, keep, 0.0, records=True)
+    gm, _, rm = orc.worker_grad(d, tm, x, y, keep, 0.0, records=True)
+    assert 0 < rp.hpre[0, 3] < 1e-11 and -1e-11 < rm.hpre[0, 3] < 0
+    assert np.linalg.norm(gp - gm) > 1e-6 * np.linalg.norm(gp)
+    gf, _ = orc.worker_grad(d, tp, x, y, keep, 0.0, forced=np.array([[0, 3, 3, 0]], np.int32))
+    assert np.linalg.norm(gf - gm) <= 1e-9 * np.linalg.norm(gm)
+    # pool gate: a window whose winner sits a hair above zero, forced shut
+    xz = x.copy().reshape(B, 8, 8)
+    xz[0, 2:4, 2:4] = [[-0.3, -0.2], [1e-12, -0.5]]
+    xn = xz.copy()
+    xn[0, 3, 2] = -1e-12
+    gz, _, rz = orc.worker_grad(d, theta, xz.reshape(B, 64), y, keep, 0.0, records=True)
+    gn, _, _ = orc.worker_grad(d, theta, xn.reshape(B, 64), y, keep, 0.0, records=True)
+    assert rz.code1[0, 5] == 2 and 0 < rz.top1[0, 5] < 1e-11
+    gf, _ = orc.worker_grad(d, theta, xz.reshape(B, 64), y, keep, 0.0,
+                            forced=np.array([[0, 1, 5, 2], [0, 1, 21, 2]], np.int32))
+    assert np.linalg.norm(gf - gn) <= 1e-9 * max(np.linalg.norm(gn), 1e-3)
