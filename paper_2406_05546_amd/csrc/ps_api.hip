@@ -76,7 +76,7 @@ Layout make_layout(const ps_config& c)
     l.d3 = k.take(n * FC1 * 4);
     l.dp2g = k.take(n * P2_SIZE * 4);
     l.dp1g = k.take(n * P1_SIZE * 4);
-    l.part = k.take((uint64_t)c.max_workers * N_CHUNK * CONV_PART * 4);
+    l.part = k.take((uint64_t)c.max_workers * N_PART * CONV_PART * 4);
     l.keep = k.take((uint64_t)c.batch * FC1);
     l.total = k.off;
     return l;

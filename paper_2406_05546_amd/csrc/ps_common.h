@@ -20,6 +20,7 @@ constexpr int OFF_W1 = 0, OFF_B1 = 144, OFF_W2 = 160, OFF_B2 = 4768, OFF_W3 = 48
 constexpr int PSTRIDE = 813312;
 constexpr int CONV_PART = OFF_W3;  // conv1 + conv2 gradient floats (4800), reduced from chunk partials
 constexpr int N_CHUNK = 8;         // image chunks per worker in the conv weight-gradient reductions
+constexpr int N_PART = 4 * N_CHUNK;  // partial slots per worker: one per (chunk, wavefront) of conv2's kernel
 
 // One worker of a batched call.
 struct WorkerMeta {
@@ -48,13 +49,39 @@ struct WorkerBuffers {
     float* d3;           // [n*B][512]      d loss / d fc1 pre-activation
     float* dp2g;         // [n*B][1568]     d loss / d pool2, zero where pool2 == 0
     float* dp1g;         // [n*B][3136]     d loss / d pool1, zero where pool1 == 0
-    float* part;         // [n][N_CHUNK][4800] chunk partials of conv1/conv2 weight gradients
+    float* part;         // [n][N_PART][4800] partial sums of conv1/conv2 weight gradients
     float* loss;         // [n] or nullptr
     int32_t n, B;
     uint32_t seed_lo, seed_hi;
     uint32_t drop_threshold;  // drop iff word < threshold
     float drop_scale;         // 1/(1-p)
 };
+
+#if defined(__HIPCC__)
+__device__ __forceinline__ const float* worker_theta(const WorkerBuffers& wb, int w)
+{
+    return wb.ring + (size_t)wb.meta[w].slot * PSTRIDE;
+}
+__device__ __forceinline__ float* worker_grad(const WorkerBuffers& wb, int w)
+{
+    return wb.queue + (size_t)wb.meta[w].q * PSTRIDE;
+}
+
+// First maximum of a 2x2 window scanned (0,0),(0,1),(1,0),(1,1); returns the winner, sets code.
+__device__ __forceinline__ float pool_first_max(float v0, float v1, float v2, float v3, int& code)
+{
+    float best = v0;
+    code = 0;
+    if (v1 > best) { best = v1; code = 1; }
+    if (v2 > best) { best = v2; code = 2; }
+    if (v3 > best) { best = v3; code = 3; }
+    return best;
+}
+#endif
+
+void launch_conv2_fwd(const WorkerBuffers& wb, hipStream_t s);
+void launch_conv2_dx(const WorkerBuffers& wb, hipStream_t s);
+void launch_conv2_dw(const WorkerBuffers& wb, hipStream_t s);
 
 // Kernels of the path, in launch order; ids index the per-kernel timing table.
 enum KernelId {

@@ -1,0 +1,267 @@
+// conv2 (16 -> 32 channels, 3x3, pad 1, on 14x14 maps) as implicit GEMMs on the gfx950 matrix cores
+// (v_mfma_f32_16x16x4_f32): forward with fused ReLU + 2x2 max pool, input gradient, and per-worker
+// weight gradient.  Zero-padded feature maps are staged in LDS as [channel][16][16] planes with a
+// plane pitch of 264 floats, so that
+//   - a 3x3 tap is a compile-time address offset (dy*16 + dx) from a lane's base address, and
+//   - the four lane quarters of an MFMA operand (four channels, pitch 264 = 8 mod 32) fall into
+//     disjoint LDS banks.
+// The 32x16x9 filter bank lives in registers for the whole block (72 VGPRs per lane) in exactly the
+// layout the MFMA B operand wants; it is read from the worker's ring slot once per block.
+#include "ps_common.h"
+
+namespace ps {
+
+namespace {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+constexpr int CHS = 264;            // LDS pitch of one padded 16x16 plane (floats)
+constexpr int P1_IMS = C1 * CHS;    // one image of pool1 planes: 4224 floats
+constexpr int D2_IMS = C2 * CHS;    // one image of conv2-gradient planes: 8448 floats
+
+__device__ __forceinline__ floatx4 mfma16(float a, float b, floatx4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+
+// Stages the 14x14 interiors of `count` images of pool1 (16 channels each) into padded planes.
+// Images at or beyond s_end are staged as zeros.  The halo must already be zero.
+__device__ __forceinline__ void stage_pool1(float* __restrict__ tile, const float* __restrict__ p1, size_t g0,
+                                            int count, int valid, int tid)
+{
+    for (int i4 = tid; i4 < count * (P1_SIZE / 4); i4 += 256) {
+        const int img = i4 / (P1_SIZE / 4), r = (i4 % (P1_SIZE / 4)) * 4;
+        const int c = r / P1_POS, pos = r % P1_POS;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (img < valid) v = *reinterpret_cast<const float4*>(p1 + (g0 + img) * P1_SIZE + r);
+        float* plane = tile + img * P1_IMS + c * CHS + 17;  // (1,1)
+        const float e[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int p = pos + j;
+            plane[(p / P1_W) * 16 + p % P1_W] = e[j];
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Forward.  GEMM rows are conv outputs ordered (pooled position, window element) so that the four
+// accumulators of a lane are one 2x2 pool window; columns are the 32 output channels (two 16-wide
+// MFMA tiles sharing the A operand); K = (tap, channel).  A block owns up to FWD_IPB images of one
+// worker and walks them FWD_G at a time (196 pooled positions = 49 row tiles per group).
+constexpr int FWD_G = 4, FWD_IPB = 16;
+
+__global__ __launch_bounds__(256, 2) void conv2_fwd_kernel(WorkerBuffers wb, int blocks_per_worker)
+{
+    __shared__ __attribute__((aligned(16))) float tile[FWD_G * P1_IMS];  // 67,584 B
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, q = lane >> 4, l16 = lane & 15;
+    const int w = blockIdx.x / blocks_per_worker, chunk = blockIdx.x % blocks_per_worker;
+    const int B = wb.B, s_begin = chunk * FWD_IPB, s_end = min(B, s_begin + FWD_IPB);
+    const float* __restrict__ W2 = worker_theta(wb, w) + OFF_W2;
+
+    // B operand of k-step s (tap = s/4, channels 4*(s%4) .. +3): lane (q, l16) holds W2[o][4*(s%4)+q][tap]
+    float wreg[36][2];
+#pragma unroll
+    for (int s = 0; s < 36; ++s)
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf) wreg[s][hf] = W2[((l16 + 16 * hf) * C1 + 4 * (s & 3) + q) * 9 + (s >> 2)];
+    const float bias0 = W2[C2 * C1 * 9 + l16], bias1 = W2[C2 * C1 * 9 + 16 + l16];
+
+    for (int i = tid; i < FWD_G * P1_IMS / 4; i += 256)
+        reinterpret_cast<float4*>(tile)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    __syncthreads();
+
+    int rot = 0;
+    for (int s0 = s_begin; s0 < s_end; s0 += FWD_G, ++rot) {
+        const size_t g0 = (size_t)w * B + s0;
+        const int valid = min(FWD_G, s_end - s0);
+        stage_pool1(tile, wb.p1, g0, FWD_G, valid, tid);
+        __syncthreads();
+        for (int t = (wave + rot) & 3; t < FWD_G * P2_POS / 4; t += 4) {
+            // A operand: lane row l16 = (pooled position 4t + l16/4, window element l16%4)
+            const int pp = 4 * t + (l16 >> 2), img = pp / P2_POS, pos = pp % P2_POS;
+            const int y = 2 * (pos / P2_W) + ((l16 >> 1) & 1), x = 2 * (pos % P2_W) + (l16 & 1);
+            const float* a = tile + img * P1_IMS + q * CHS + y * 16 + x;
+            floatx4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < 36; ++s) {
+                const float av = a[4 * (s & 3) * CHS + ((s >> 2) / 3) * 16 + (s >> 2) % 3];
+                acc0 = mfma16(av, wreg[s][0], acc0);
+                acc1 = mfma16(av, wreg[s][1], acc1);
+            }
+            // lane (q, l16) now holds the 2x2 window of pooled position 4t + q for channels l16, l16+16
+            const int ppo = 4 * t + q, img_o = ppo / P2_POS, pos_o = ppo % P2_POS;
+            if (img_o < valid) {
+                const size_t out = (g0 + img_o) * P2_SIZE + pos_o;
+                int code;
+                float best = pool_first_max(acc0[0] + bias0, acc0[1] + bias0, acc0[2] + bias0, acc0[3] + bias0, code);
+                wb.p2[out + l16 * P2_POS] = fmaxf(best, 0.f);
+                wb.am2[out + l16 * P2_POS] = (uint8_t)(code | (best > 0.f ? 4 : 0));
+                best = pool_first_max(acc1[0] + bias1, acc1[1] + bias1, acc1[2] + bias1, acc1[3] + bias1, code);
+                wb.p2[out + (l16 + 16) * P2_POS] = fmaxf(best, 0.f);
+                wb.am2[out + (l16 + 16) * P2_POS] = (uint8_t)(code | (best > 0.f ? 4 : 0));
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Scatters the gated pool2 gradient of one image to the window winners of padded planes
+// d2[o][16][16] (interior at (1,1)); with CLEAR the same positions are set back to zero.
+template <bool CLEAR>
+__device__ __forceinline__ void scatter_d2(float* __restrict__ d2, const WorkerBuffers& wb, size_t g, int tid)
+{
+    for (int i = tid; i < P2_SIZE; i += 256) {
+        const int o = i / P2_POS, p = i % P2_POS;
+        const int code = wb.am2[g * P2_SIZE + i] & 3;
+        const int at = o * CHS + (2 * (p / P2_W) + (code >> 1) + 1) * 16 + 2 * (p % P2_W) + (code & 1) + 1;
+        d2[at] = CLEAR ? 0.f : wb.dp2g[g * P2_SIZE + i];
+    }
+}
+
+// Input gradient: d pool1[c][y][x] = sum_{o,dy,dx} d2pad[o][y+2-dy][x+2-dx] * W2[o][c][dy][dx], zeroed
+// where pool1 == 0.  GEMM rows are the 196 positions of an image (16 per tile), columns the 16 input
+// channels, K = (flipped tap, output channel) = 288.  A block owns up to DX_IPB images of one worker
+// and walks them DX_G at a time.
+constexpr int DX_G = 2, DX_IPB = 16;
+
+__global__ __launch_bounds__(256, 2) void conv2_dx_kernel(WorkerBuffers wb, int blocks_per_worker)
+{
+    __shared__ __attribute__((aligned(16))) float tile[DX_G * D2_IMS];  // 67,584 B
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, q = lane >> 4, l16 = lane & 15;
+    const int w = blockIdx.x / blocks_per_worker, chunk = blockIdx.x % blocks_per_worker;
+    const int B = wb.B, s_begin = chunk * DX_IPB, s_end = min(B, s_begin + DX_IPB);
+    const float* __restrict__ W2 = worker_theta(wb, w) + OFF_W2;
+
+    // B operand of k-step s (flipped tap t' = s/8, output channels 4*(s%8) .. +3): lane (q, l16) holds
+    // W2[4*(s%8)+q][c = l16][8 - t']
+    float wreg[72];
+#pragma unroll
+    for (int s = 0; s < 72; ++s) wreg[s] = W2[((4 * (s & 7) + q) * C1 + l16) * 9 + 8 - (s >> 3)];
+
+    for (int i = tid; i < DX_G * D2_IMS / 4; i += 256)
+        reinterpret_cast<float4*>(tile)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    __syncthreads();
+
+    int rot = 0;
+    for (int s0 = s_begin; s0 < s_end; s0 += DX_G, ++rot) {
+        const size_t g0 = (size_t)w * B + s0;
+        const int valid = min(DX_G, s_end - s0);
+        for (int img = 0; img < valid; ++img) scatter_d2<false>(tile + img * D2_IMS, wb, g0 + img, tid);
+        __syncthreads();
+        for (int t = (wave + rot) & 3; t < (DX_G * P1_POS + 15) / 16; t += 4) {
+            // A operand: lane row l16 = position 16t + l16 of the group (reads of a row beyond the group
+            // are redirected to position 0 and their results dropped)
+            const int m = 16 * t + l16, mm = m < DX_G * P1_POS ? m : 0;
+            const int img = mm / P1_POS, pos = mm % P1_POS;
+            const float* a = tile + img * D2_IMS + q * CHS + (pos / P1_W) * 16 + pos % P1_W;
+            floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < 72; ++s)
+                acc = mfma16(a[4 * (s & 7) * CHS + ((s >> 3) / 3) * 16 + (s >> 3) % 3], wreg[s], acc);
+            // lane (q, l16) holds channel l16 at positions 16t + 4q .. +3 (never straddling an image)
+            const int mo = 16 * t + 4 * q, img_o = mo / P1_POS, pos_o = mo % P1_POS;
+            if (mo < DX_G * P1_POS && img_o < valid) {
+                const size_t at = (g0 + img_o) * P1_SIZE + l16 * P1_POS + pos_o;
+                const uint32_t gate = *reinterpret_cast<const uint32_t*>(wb.am1 + at);
+                float4 o;
+                o.x = (gate & 0x00000004u) ? acc[0] : 0.f;
+                o.y = (gate & 0x00000400u) ? acc[1] : 0.f;
+                o.z = (gate & 0x00040000u) ? acc[2] : 0.f;
+                o.w = (gate & 0x04000000u) ? acc[3] : 0.f;
+                *reinterpret_cast<float4*>(wb.dp1g + at) = o;
+            }
+        }
+        __syncthreads();
+        for (int img = 0; img < valid; ++img) scatter_d2<true>(tile + img * D2_IMS, wb, g0 + img, tid);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Weight gradient: d W2[o][c][dy][dx] = sum over the worker's images and positions of
+// d2[o][y][x] * pool1pad[c][y+dy][x+dx];  d b2[o] = sum d2[o].  GEMM rows are the 32 output channels
+// (two tiles), columns (tap, input channel) (nine tiles), K = positions, four per MFMA step.  A block
+// owns one chunk of a worker's images; its four wavefronts split every image's 49 k-steps and keep
+// their 18 accumulator tiles across images; each wavefront's sum goes to its own partial slot.
+__global__ __launch_bounds__(256, 2) void conv2_dw_kernel(WorkerBuffers wb)
+{
+    __shared__ __attribute__((aligned(16))) float d2[D2_IMS];   // 33,792 B
+    __shared__ __attribute__((aligned(16))) float p1t[P1_IMS];  // 16,896 B
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, q = lane >> 4, l16 = lane & 15;
+    const int w = blockIdx.x, chunk = blockIdx.y, B = wb.B;
+    const int per = (B + N_CHUNK - 1) / N_CHUNK;
+    const int s_begin = chunk * per, s_end = min(B, s_begin + per);
+
+    floatx4 acc[2][9];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int j = 0; j < 9; ++j) acc[mt][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+    float sum0 = 0.f, sum1 = 0.f;
+
+    for (int i = tid; i < D2_IMS / 4; i += 256) reinterpret_cast<float4*>(d2)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int i = tid; i < P1_IMS / 4; i += 256) reinterpret_cast<float4*>(p1t)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    __syncthreads();
+
+    int rot = 0;
+    for (int s = s_begin; s < s_end; ++s, ++rot) {
+        const size_t g = (size_t)w * B + s;
+        scatter_d2<false>(d2, wb, g, tid);
+        stage_pool1(p1t, wb.p1, g, 1, 1, tid);
+        __syncthreads();
+        for (int ks = (wave + rot) & 3; ks < P1_POS / 4; ks += 4) {
+            const int pos = 4 * ks + q, off = (pos / P1_W) * 16 + pos % P1_W;
+            const float a0 = d2[l16 * CHS + off + 17], a1 = d2[(l16 + 16) * CHS + off + 17];
+            sum0 += a0;
+            sum1 += a1;
+            const float* b = p1t + l16 * CHS + off;
+#pragma unroll
+            for (int j = 0; j < 9; ++j) {
+                const float bv = b[(j / 3) * 16 + j % 3];
+                acc[0][j] = mfma16(a0, bv, acc[0][j]);
+                acc[1][j] = mfma16(a1, bv, acc[1][j]);
+            }
+        }
+        __syncthreads();
+        scatter_d2<true>(d2, wb, g, tid);
+    }
+
+    // accumulator i of tile (mt, j): output channel 16*mt + 4q + i, input channel l16, tap j
+    float* part = wb.part + ((size_t)w * N_PART + chunk * 4 + wave) * CONV_PART;
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int j = 0; j < 9; ++j)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) part[OFF_W2 + ((16 * mt + 4 * q + i) * C1 + l16) * 9 + j] = acc[mt][j][i];
+    sum0 += __shfl_xor(sum0, 16, 64);
+    sum0 += __shfl_xor(sum0, 32, 64);
+    sum1 += __shfl_xor(sum1, 16, 64);
+    sum1 += __shfl_xor(sum1, 32, 64);
+    if (q == 0) {
+        part[OFF_B2 + l16] = sum0;
+        part[OFF_B2 + 16 + l16] = sum1;
+    }
+}
+
+}  // namespace
+
+void launch_conv2_fwd(const WorkerBuffers& wb, hipStream_t s)
+{
+    const int bpw = (wb.B + FWD_IPB - 1) / FWD_IPB;
+    hipLaunchKernelGGL(conv2_fwd_kernel, dim3(wb.n * bpw), dim3(256), 0, s, wb, bpw);
+}
+
+void launch_conv2_dx(const WorkerBuffers& wb, hipStream_t s)
+{
+    const int bpw = (wb.B + DX_IPB - 1) / DX_IPB;
+    hipLaunchKernelGGL(conv2_dx_kernel, dim3(wb.n * bpw), dim3(256), 0, s, wb, bpw);
+}
+
+void launch_conv2_dw(const WorkerBuffers& wb, hipStream_t s)
+{
+    hipLaunchKernelGGL(conv2_dw_kernel, dim3(wb.n, N_CHUNK), dim3(256), 0, s, wb);
+}
+
+}  // namespace ps

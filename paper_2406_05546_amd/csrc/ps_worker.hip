@@ -10,26 +10,6 @@ namespace ps {
 
 namespace {
 
-__device__ __forceinline__ const float* worker_theta(const WorkerBuffers& wb, int w)
-{
-    return wb.ring + (size_t)wb.meta[w].slot * PSTRIDE;
-}
-__device__ __forceinline__ float* worker_grad(const WorkerBuffers& wb, int w)
-{
-    return wb.queue + (size_t)wb.meta[w].q * PSTRIDE;
-}
-
-// First maximum of a 2x2 window scanned (0,0),(0,1),(1,0),(1,1); returns the winner, sets code.
-__device__ __forceinline__ float pool_first_max(float v0, float v1, float v2, float v3, int& code)
-{
-    float best = v0;
-    code = 0;
-    if (v1 > best) { best = v1; code = 1; }
-    if (v2 > best) { best = v2; code = 2; }
-    if (v3 > best) { best = v3; code = 3; }
-    return best;
-}
-
 // ---------------------------------------------------------------------------------------------
 // conv1 (1 -> 16, 3x3, pad 1) + ReLU + 2x2 max pool.  One block per image; a thread owns one
 // pooled position and walks the 16 output channels with its 4x4 input patch in registers.
@@ -74,60 +54,6 @@ __global__ __launch_bounds__(256) void conv1_fwd_kernel(WorkerBuffers wb)
         const size_t out = (size_t)g * P1_SIZE + o * P1_POS + t;
         wb.p1[out] = fmaxf(best, 0.f);
         wb.am1[out] = (uint8_t)(code | (best > 0.f ? 4 : 0));
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
-// conv2 (16 -> 32, 3x3, pad 1) + ReLU + 2x2 max pool.  One block per image: the zero-padded pool1
-// map and the 32x16x9 filter bank sit in LDS; a thread owns one pooled position for 8 channels.
-__global__ __launch_bounds__(256) void conv2_fwd_kernel(WorkerBuffers wb)
-{
-    __shared__ float ps[C1 * 256];              // [c][16][16], interior at (1,1)
-    __shared__ float ws[C2 * C1 * 9 + C2];      // conv2.W then conv2.b
-    const int g = blockIdx.x, w = g / wb.B, t = threadIdx.x;
-    const float* theta = worker_theta(wb, w);
-    for (int i = t; i < C1 * 256; i += 256) {
-        const int c = i >> 8, yy = ((i >> 4) & 15) - 1, xx = (i & 15) - 1;
-        ps[i] = (yy >= 0 && yy < 14 && xx >= 0 && xx < 14) ? wb.p1[(size_t)g * P1_SIZE + c * P1_POS + yy * 14 + xx] : 0.f;
-    }
-    for (int i = t; i < C2 * C1 * 9 + C2; i += 256) ws[i] = theta[OFF_W2 + i];
-    __syncthreads();
-    const int p = t & 63, og = t >> 6;
-    if (p >= P2_POS) return;
-    const int py = p / P2_W, px = p % P2_W;
-    float acc[8][4];
-#pragma unroll
-    for (int oo = 0; oo < 8; ++oo)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) acc[oo][q] = ws[C2 * C1 * 9 + og * 8 + oo];
-    for (int c = 0; c < C1; ++c) {
-        float patch[4][4];
-#pragma unroll
-        for (int a = 0; a < 4; ++a)
-#pragma unroll
-            for (int b = 0; b < 4; ++b) patch[a][b] = ps[c * 256 + (2 * py + a) * 16 + 2 * px + b];
-#pragma unroll
-        for (int oo = 0; oo < 8; ++oo) {
-            const float* k = ws + ((og * 8 + oo) * C1 + c) * 9;
-#pragma unroll
-            for (int dy = 0; dy < 3; ++dy)
-#pragma unroll
-                for (int dx = 0; dx < 3; ++dx) {
-                    const float kv = k[dy * 3 + dx];
-#pragma unroll
-                    for (int a = 0; a < 2; ++a)
-#pragma unroll
-                        for (int b = 0; b < 2; ++b) acc[oo][a * 2 + b] = fmaf(kv, patch[a + dy][b + dx], acc[oo][a * 2 + b]);
-                }
-        }
-    }
-#pragma unroll
-    for (int oo = 0; oo < 8; ++oo) {
-        int code;
-        const float best = pool_first_max(acc[oo][0], acc[oo][1], acc[oo][2], acc[oo][3], code);
-        const size_t out = (size_t)g * P2_SIZE + (og * 8 + oo) * P2_POS + p;
-        wb.p2[out] = fmaxf(best, 0.f);
-        wb.am2[out] = (uint8_t)(code | (best > 0.f ? 4 : 0));
     }
 }
 
@@ -282,99 +208,6 @@ __global__ __launch_bounds__(256) void fc2_grad_kernel(WorkerBuffers wb)
 }
 
 // ---------------------------------------------------------------------------------------------
-// conv2 input gradient.  The gradient at the conv2 pre-activation is the pool2 gradient routed to
-// each window's winner (zero elsewhere); d pool1[c][y][x] = sum_{o,dy,dx} d2[o][y+1-dy][x+1-dx] *
-// W2[o][c][dy][dx], then zeroed where pool1 == 0 (ReLU gate of conv1).  One block per image.
-__global__ __launch_bounds__(256) void conv2_dx_kernel(WorkerBuffers wb)
-{
-    __shared__ float d2[C2 * 256];                                         // [o][16][16], interior at (1,1)
-    __shared__ __attribute__((aligned(16))) float wt[C2 * 9 * C1];         // [o][tap][c]
-    const int g = blockIdx.x, w = g / wb.B, t = threadIdx.x;
-    const float* W2 = worker_theta(wb, w) + OFF_W2;
-    for (int i = t; i < C2 * 256; i += 256) d2[i] = 0.f;
-    for (int i = t; i < C2 * C1 * 9; i += 256) {
-        const int o = i / 144, c = (i / 9) % 16, tap = i % 9;
-        wt[(o * 9 + tap) * C1 + c] = W2[i];
-    }
-    __syncthreads();
-    for (int i = t; i < P2_SIZE; i += 256) {
-        const int o = i / P2_POS, p = i % P2_POS, py = p / P2_W, px = p % P2_W;
-        const int code = wb.am2[(size_t)g * P2_SIZE + i] & 3;
-        d2[o * 256 + (2 * py + (code >> 1) + 1) * 16 + 2 * px + (code & 1) + 1] = wb.dp2g[(size_t)g * P2_SIZE + i];
-    }
-    __syncthreads();
-    for (int item = t; item < P1_POS * 4; item += 256) {
-        const int pos = item % P1_POS, cg = item / P1_POS, y = pos / P1_W, x = pos % P1_W;
-        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (int o = 0; o < C2; ++o)
-#pragma unroll
-            for (int dy = 0; dy < 3; ++dy)
-#pragma unroll
-                for (int dx = 0; dx < 3; ++dx) {
-                    const float d = d2[o * 256 + (y + 2 - dy) * 16 + x + 2 - dx];
-                    const float4 k = *reinterpret_cast<const float4*>(wt + (o * 9 + dy * 3 + dx) * C1 + cg * 4);
-                    acc.x = fmaf(d, k.x, acc.x); acc.y = fmaf(d, k.y, acc.y);
-                    acc.z = fmaf(d, k.z, acc.z); acc.w = fmaf(d, k.w, acc.w);
-                }
-        const float r[4] = {acc.x, acc.y, acc.z, acc.w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const size_t at = (size_t)g * P1_SIZE + (cg * 4 + i) * P1_POS + pos;
-            wb.dp1g[at] = (wb.am1[at] & 4) ? r[i] : 0.f;
-        }
-    }
-}
-
-// conv2 weight gradient: d W2[o][c][dy][dx] = sum over images and positions of
-// d2[o][y][x] * pool1pad[c][y+dy][x+dx].  Only each window's winner carries gradient, so a thread
-// walks the 49 windows of its output channel and gathers.  grid (n, N_CHUNK): a block sums one
-// chunk of the worker's images; chunk partials are reduced in fixed order afterwards.
-__global__ __launch_bounds__(256) void conv2_dw_kernel(WorkerBuffers wb)
-{
-    __shared__ float ps[C1 * 256];
-    __shared__ float dv[P2_SIZE];
-    __shared__ uint16_t dpos[P2_SIZE];
-    const int w = blockIdx.x, chunk = blockIdx.y, t = threadIdx.x, B = wb.B;
-    const int per = (B + N_CHUNK - 1) / N_CHUNK;
-    const int s0 = chunk * per, s1 = min(B, s0 + per);
-    const int o = t >> 3, j = t & 7;
-    int off[18];
-#pragma unroll
-    for (int i = 0; i < 18; ++i) {
-        const int ct = j + 8 * i, c = ct / 9, tap = ct % 9;
-        off[i] = c * 256 + (tap / 3) * 16 + tap % 3;
-    }
-    float acc[18], accb = 0.f;
-#pragma unroll
-    for (int i = 0; i < 18; ++i) acc[i] = 0.f;
-    for (int s = s0; s < s1; ++s) {
-        const size_t g = (size_t)w * B + s;
-        __syncthreads();
-        for (int i = t; i < C1 * 256; i += 256) {
-            const int c = i >> 8, yy = ((i >> 4) & 15) - 1, xx = (i & 15) - 1;
-            ps[i] = (yy >= 0 && yy < 14 && xx >= 0 && xx < 14) ? wb.p1[g * P1_SIZE + c * P1_POS + yy * 14 + xx] : 0.f;
-        }
-        for (int i = t; i < P2_SIZE; i += 256) {
-            const int p = i % P2_POS, py = p / P2_W, px = p % P2_W;
-            const int code = wb.am2[g * P2_SIZE + i] & 3;
-            dv[i] = wb.dp2g[g * P2_SIZE + i];
-            dpos[i] = (uint16_t)((2 * py + (code >> 1)) * 16 + 2 * px + (code & 1));
-        }
-        __syncthreads();
-        for (int p = 0; p < P2_POS; ++p) {
-            const float v = dv[o * P2_POS + p];
-            const int base = dpos[o * P2_POS + p];
-            accb += v;
-#pragma unroll
-            for (int i = 0; i < 18; ++i) acc[i] = fmaf(v, ps[base + off[i]], acc[i]);
-        }
-    }
-    float* part = wb.part + ((size_t)w * N_CHUNK + chunk) * CONV_PART;
-#pragma unroll
-    for (int i = 0; i < 18; ++i) part[OFF_W2 + o * 144 + j + 8 * i] = acc[i];
-    if (j == 0) part[OFF_B2 + o] = accb;
-}
-
 // conv1 weight gradient: d W1[o][dy][dx] = sum over images and pooled positions of
 // dpool1g[o][p] * xpad[winner(p) + (dy,dx)].  grid (n, N_CHUNK); 16 lanes share an output channel.
 __global__ __launch_bounds__(256) void conv1_dw_kernel(WorkerBuffers wb)
@@ -414,23 +247,29 @@ __global__ __launch_bounds__(256) void conv1_dw_kernel(WorkerBuffers wb)
         accb += __shfl_xor(accb, m, 64);
     }
     if (l16 == 0) {
-        float* part = wb.part + ((size_t)w * N_CHUNK + chunk) * CONV_PART;
+        float* part = wb.part + ((size_t)w * N_PART + chunk * 4) * CONV_PART;
 #pragma unroll
         for (int i = 0; i < 9; ++i) part[OFF_W1 + o * 9 + i] = acc[i];
         part[OFF_B1 + o] = accb;
     }
 }
 
-// Sums the chunk partials in chunk order into the worker's queue entry (conv1 and conv2 tensors).
+// Sums the partial slots in fixed order into the worker's queue entry: conv1 tensors have one partial
+// per chunk (slot 4*chunk), conv2 tensors one per (chunk, wavefront).
 __global__ __launch_bounds__(256) void conv_grad_reduce_kernel(WorkerBuffers wb)
 {
     const int w = blockIdx.x;
     float* grad = worker_grad(wb, w);
-    const float* part = wb.part + (size_t)w * N_CHUNK * CONV_PART;
+    const float* part = wb.part + (size_t)w * N_PART * CONV_PART;
     for (int i = threadIdx.x; i < CONV_PART; i += 256) {
         float sum = 0.f;
+        if (i < OFF_W2) {
 #pragma unroll
-        for (int c = 0; c < N_CHUNK; ++c) sum += part[(size_t)c * CONV_PART + i];
+            for (int c = 0; c < N_CHUNK; ++c) sum += part[(size_t)c * 4 * CONV_PART + i];
+        } else {
+#pragma unroll
+            for (int c = 0; c < N_PART; ++c) sum += part[(size_t)c * CONV_PART + i];
+        }
         grad[i] = sum;
     }
 }
@@ -465,7 +304,7 @@ hipError_t launch_worker_forward(const WorkerBuffers& wb, hipStream_t s, Profile
     const int N = wb.n * wb.B;
     if (N <= 0) return hipSuccess;
     PS_TIMED(K_CONV1_FWD, hipLaunchKernelGGL(conv1_fwd_kernel, dim3(N), dim3(256), 0, s, wb));
-    PS_TIMED(K_CONV2_FWD, hipLaunchKernelGGL(conv2_fwd_kernel, dim3(N), dim3(256), 0, s, wb));
+    PS_TIMED(K_CONV2_FWD, launch_conv2_fwd(wb, s));
     GemmShape sh{FC1, wb.B, P2_SIZE, P2_SIZE, P2_SIZE};
     PS_TIMED(K_FC1_FWD, hipLaunchKernelGGL((gemm_f32_mfma<true, true, Fc1FwdEpi>), gemm_grid(sh.M, sh.N, wb.n),
                                            dim3(256), 0, s, sh, Fc1FwdEpi{wb}));
@@ -484,8 +323,8 @@ hipError_t launch_worker_backward(const WorkerBuffers& wb, hipStream_t s, Profil
     GemmShape dx{P2_SIZE, wb.B, FC1, P2_SIZE, FC1};
     PS_TIMED(K_FC1_DX, hipLaunchKernelGGL((gemm_f32_mfma<false, true, Fc1DxEpi>), gemm_grid(dx.M, dx.N, wb.n),
                                           dim3(256), 0, s, dx, Fc1DxEpi{wb}));
-    PS_TIMED(K_CONV2_DW, hipLaunchKernelGGL(conv2_dw_kernel, dim3(wb.n, N_CHUNK), dim3(256), 0, s, wb));
-    PS_TIMED(K_CONV2_DX, hipLaunchKernelGGL(conv2_dx_kernel, dim3(N), dim3(256), 0, s, wb));
+    PS_TIMED(K_CONV2_DW, launch_conv2_dw(wb, s));
+    PS_TIMED(K_CONV2_DX, launch_conv2_dx(wb, s));
     PS_TIMED(K_CONV1_DW, hipLaunchKernelGGL(conv1_dw_kernel, dim3(wb.n, N_CHUNK), dim3(256), 0, s, wb));
     PS_TIMED(K_CONV_REDUCE, hipLaunchKernelGGL(conv_grad_reduce_kernel, dim3(wb.n), dim3(256), 0, s, wb));
     return hipGetLastError();
