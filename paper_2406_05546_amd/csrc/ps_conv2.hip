@@ -24,25 +24,77 @@ __device__ __forceinline__ floatx4 mfma16(float a, float b, floatx4 c)
     return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
 }
 
-// Stages the 14x14 interiors of `count` images of pool1 (16 channels each) into padded planes.
-// Images at or beyond s_end are staged as zeros.  The halo must already be zero.
-__device__ __forceinline__ void stage_pool1(float* __restrict__ tile, const float* __restrict__ p1, size_t g0,
-                                            int count, int valid, int tid)
-{
-    for (int i4 = tid; i4 < count * (P1_SIZE / 4); i4 += 256) {
-        const int img = i4 / (P1_SIZE / 4), r = (i4 % (P1_SIZE / 4)) * 4;
-        const int c = r / P1_POS, pos = r % P1_POS;
-        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (img < valid) v = *reinterpret_cast<const float4*>(p1 + (g0 + img) * P1_SIZE + r);
-        float* plane = tile + img * P1_IMS + c * CHS + 17;  // (1,1)
-        const float e[4] = {v.x, v.y, v.z, v.w};
+// Staging is split in two so that the global loads of the next group of images are in flight while
+// the matrix cores work on the current one: prefetch_* issues the loads into registers, commit_*
+// writes the registers into the padded LDS planes after the barrier that ends the current group.
+
+// pool1 planes of COUNT images (16 channels, 14x14 interiors); NV float4 per thread.
+template <int COUNT>
+struct Pool1Stage {
+    static constexpr int N4 = COUNT * (P1_SIZE / 4), NV = (N4 + 255) / 256;
+    float4 v[NV];
+    // images [g0, g0 + valid) exist; the rest of the group is staged as zeros
+    __device__ __forceinline__ void prefetch(const float* __restrict__ p1, size_t g0, int valid, int tid)
+    {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int p = pos + j;
-            plane[(p / P1_W) * 16 + p % P1_W] = e[j];
+        for (int k = 0; k < NV; ++k) {
+            const int i4 = tid + 256 * k;
+            v[k] = (i4 < N4 && i4 / (P1_SIZE / 4) < valid)
+                       ? *reinterpret_cast<const float4*>(p1 + g0 * P1_SIZE + (size_t)i4 * 4)
+                       : make_float4(0.f, 0.f, 0.f, 0.f);
         }
     }
-}
+    __device__ __forceinline__ void commit(float* __restrict__ tile, int tid) const
+    {
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {
+            const int i4 = tid + 256 * k;
+            if (i4 >= N4) break;
+            const int img = i4 / (P1_SIZE / 4), r = (i4 % (P1_SIZE / 4)) * 4, c = r / P1_POS, pos = r % P1_POS;
+            float* plane = tile + img * P1_IMS + c * CHS + 17;  // (1,1)
+            const float e[4] = {v[k].x, v[k].y, v[k].z, v[k].w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) plane[((pos + j) / P1_W) * 16 + (pos + j) % P1_W] = e[j];
+        }
+    }
+};
+
+// Gated pool2 gradient of COUNT images, routed to the window winners of padded planes
+// d2[o][16][16] (interior at (1,1)).  clear() zeroes exactly the elements the last commit wrote.
+template <int COUNT>
+struct D2Stage {
+    static constexpr int N = COUNT * P2_SIZE, NV = (N + 255) / 256;
+    float v[NV];
+    uint8_t code[NV];
+    uint16_t at[NV];
+    __device__ __forceinline__ void prefetch(const WorkerBuffers& wb, size_t g0, int valid, int tid)
+    {
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {
+            const int i = tid + 256 * k;
+            const bool ok = i < N && i / P2_SIZE < valid;
+            v[k] = ok ? wb.dp2g[g0 * P2_SIZE + i] : 0.f;
+            code[k] = ok ? wb.am2[g0 * P2_SIZE + i] : 0;
+        }
+    }
+    __device__ __forceinline__ void commit(float* __restrict__ d2, int tid)
+    {
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {
+            const int i = tid + 256 * k;
+            if (i >= N) break;
+            const int img = i / P2_SIZE, r = i % P2_SIZE, o = r / P2_POS, p = r % P2_POS, cd = code[k] & 3;
+            at[k] = (uint16_t)(img * D2_IMS + o * CHS + (2 * (p / P2_W) + (cd >> 1) + 1) * 16 + 2 * (p % P2_W) + (cd & 1) + 1);
+            d2[at[k]] = v[k];
+        }
+    }
+    __device__ __forceinline__ void clear(float* __restrict__ d2, int tid) const
+    {
+#pragma unroll
+        for (int k = 0; k < NV; ++k)
+            if (tid + 256 * k < N) d2[at[k]] = 0.f;
+    }
+};
 
 // ---------------------------------------------------------------------------------------------
 // Forward.  GEMM rows are conv outputs ordered (pooled position, window element) so that the four
@@ -71,12 +123,15 @@ __global__ __launch_bounds__(256, 2) void conv2_fwd_kernel(WorkerBuffers wb, int
         reinterpret_cast<float4*>(tile)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
     __syncthreads();
 
+    Pool1Stage<FWD_G> stage;
+    stage.prefetch(wb.p1, (size_t)w * B + s_begin, min(FWD_G, s_end - s_begin), tid);
     int rot = 0;
     for (int s0 = s_begin; s0 < s_end; s0 += FWD_G, ++rot) {
         const size_t g0 = (size_t)w * B + s0;
         const int valid = min(FWD_G, s_end - s0);
-        stage_pool1(tile, wb.p1, g0, FWD_G, valid, tid);
+        stage.commit(tile, tid);
         __syncthreads();
+        if (s0 + FWD_G < s_end) stage.prefetch(wb.p1, g0 + FWD_G, min(FWD_G, s_end - s0 - FWD_G), tid);
         for (int t = (wave + rot) & 3; t < FWD_G * P2_POS / 4; t += 4) {
             // A operand: lane row l16 = (pooled position 4t + l16/4, window element l16%4)
             const int pp = 4 * t + (l16 >> 2), img = pp / P2_POS, pos = pp % P2_POS;
@@ -107,19 +162,6 @@ __global__ __launch_bounds__(256, 2) void conv2_fwd_kernel(WorkerBuffers wb, int
 }
 
 // ---------------------------------------------------------------------------------------------
-// Scatters the gated pool2 gradient of one image to the window winners of padded planes
-// d2[o][16][16] (interior at (1,1)); with CLEAR the same positions are set back to zero.
-template <bool CLEAR>
-__device__ __forceinline__ void scatter_d2(float* __restrict__ d2, const WorkerBuffers& wb, size_t g, int tid)
-{
-    for (int i = tid; i < P2_SIZE; i += 256) {
-        const int o = i / P2_POS, p = i % P2_POS;
-        const int code = wb.am2[g * P2_SIZE + i] & 3;
-        const int at = o * CHS + (2 * (p / P2_W) + (code >> 1) + 1) * 16 + 2 * (p % P2_W) + (code & 1) + 1;
-        d2[at] = CLEAR ? 0.f : wb.dp2g[g * P2_SIZE + i];
-    }
-}
-
 // Input gradient: d pool1[c][y][x] = sum_{o,dy,dx} d2pad[o][y+2-dy][x+2-dx] * W2[o][c][dy][dx], zeroed
 // where pool1 == 0.  GEMM rows are the 196 positions of an image (16 per tile), columns the 16 input
 // channels, K = (flipped tap, output channel) = 288.  A block owns up to DX_IPB images of one worker
@@ -144,12 +186,15 @@ __global__ __launch_bounds__(256, 2) void conv2_dx_kernel(WorkerBuffers wb, int 
         reinterpret_cast<float4*>(tile)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
     __syncthreads();
 
+    D2Stage<DX_G> stage;
+    stage.prefetch(wb, (size_t)w * B + s_begin, min(DX_G, s_end - s_begin), tid);
     int rot = 0;
     for (int s0 = s_begin; s0 < s_end; s0 += DX_G, ++rot) {
         const size_t g0 = (size_t)w * B + s0;
         const int valid = min(DX_G, s_end - s0);
-        for (int img = 0; img < valid; ++img) scatter_d2<false>(tile + img * D2_IMS, wb, g0 + img, tid);
+        stage.commit(tile, tid);
         __syncthreads();
+        if (s0 + DX_G < s_end) stage.prefetch(wb, g0 + DX_G, min(DX_G, s_end - s0 - DX_G), tid);
         for (int t = (wave + rot) & 3; t < (DX_G * P1_POS + 15) / 16; t += 4) {
             // A operand: lane row l16 = position 16t + l16 of the group (reads of a row beyond the group
             // are redirected to position 0 and their results dropped)
@@ -174,7 +219,7 @@ __global__ __launch_bounds__(256, 2) void conv2_dx_kernel(WorkerBuffers wb, int 
             }
         }
         __syncthreads();
-        for (int img = 0; img < valid; ++img) scatter_d2<true>(tile + img * D2_IMS, wb, g0 + img, tid);
+        stage.clear(tile, tid);  // the same thread rewrites these windows at the next commit
     }
 }
 
@@ -204,12 +249,22 @@ __global__ __launch_bounds__(256, 2) void conv2_dw_kernel(WorkerBuffers wb)
     for (int i = tid; i < P1_IMS / 4; i += 256) reinterpret_cast<float4*>(p1t)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
     __syncthreads();
 
+    D2Stage<1> sd;
+    Pool1Stage<1> sp;
+    if (s_begin < s_end) {
+        sd.prefetch(wb, (size_t)w * B + s_begin, 1, tid);
+        sp.prefetch(wb.p1, (size_t)w * B + s_begin, 1, tid);
+    }
     int rot = 0;
     for (int s = s_begin; s < s_end; ++s, ++rot) {
         const size_t g = (size_t)w * B + s;
-        scatter_d2<false>(d2, wb, g, tid);
-        stage_pool1(p1t, wb.p1, g, 1, 1, tid);
+        sd.commit(d2, tid);
+        sp.commit(p1t, tid);
         __syncthreads();
+        if (s + 1 < s_end) {
+            sd.prefetch(wb, g + 1, 1, tid);
+            sp.prefetch(wb.p1, g + 1, 1, tid);
+        }
         for (int ks = (wave + rot) & 3; ks < P1_POS / 4; ks += 4) {
             const int pos = 4 * ks + q, off = (pos / P1_W) * 16 + pos % P1_W;
             const float a0 = d2[l16 * CHS + off + 17], a1 = d2[(l16 + 16) * CHS + off + 17];
@@ -224,7 +279,7 @@ __global__ __launch_bounds__(256, 2) void conv2_dw_kernel(WorkerBuffers wb)
             }
         }
         __syncthreads();
-        scatter_d2<true>(d2, wb, g, tid);
+        sd.clear(d2, tid);
     }
 
     // accumulator i of tile (mt, j): output channel 16*mt + 4q + i, input channel l16, tap j
