@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <algorithm>
 #include <vector>
 
 namespace ps {
@@ -44,12 +45,11 @@ struct WorkerBuffers {
     float* ht;           // [n*B][512]      fc1 -> ReLU -> dropout
     float* z;            // [n*B][10]       logits
     int32_t* pred;       // [n*B]
-    float* loss_i;       // [n*B]
-    float* d4;           // [n*B][10]       d loss / d logits (already / B)
     float* d3;           // [n*B][512]      d loss / d fc1 pre-activation
     float* dp2g;         // [n*B][1568]     d loss / d pool2, zero where pool2 == 0
     float* dp1g;         // [n*B][3136]     d loss / d pool1, zero where pool1 == 0
     float* part;         // [n][N_PART][4800] partial sums of conv1/conv2 weight gradients
+    float* fpart;        // [n][4*split][FC2_PART] partial sums of the fc2 kernel's wavefronts
     float* loss;         // [n] or nullptr
     int32_t n, B;
     uint32_t seed_lo, seed_hi;
@@ -79,14 +79,25 @@ __device__ __forceinline__ float pool_first_max(float v0, float v1, float v2, fl
 }
 #endif
 
+// One partial slot of the fc2 kernel: d W4 [10][512], d b4 [10], d b3 [512], summed loss.
+constexpr int FC2_PART_B4 = NCLS * FC1, FC2_PART_B3 = FC2_PART_B4 + NCLS, FC2_PART_LOSS = FC2_PART_B3 + FC1,
+              FC2_PART = 5648;
+int fc2_split(int n);  // blocks per worker of the fc2 kernel (4 partial slots each)
+
+void launch_conv1_fwd(const WorkerBuffers& wb, hipStream_t s);
+void launch_conv1_dw(const WorkerBuffers& wb, hipStream_t s);
+void launch_fc1_fwd(const WorkerBuffers& wb, hipStream_t s);
+void launch_fc1_dw(const WorkerBuffers& wb, hipStream_t s);
+void launch_fc1_dx(const WorkerBuffers& wb, hipStream_t s);
+void launch_fc2(const WorkerBuffers& wb, hipStream_t s);
 void launch_conv2_fwd(const WorkerBuffers& wb, hipStream_t s);
 void launch_conv2_dx(const WorkerBuffers& wb, hipStream_t s);
 void launch_conv2_dw(const WorkerBuffers& wb, hipStream_t s);
 
 // Kernels of the path, in launch order; ids index the per-kernel timing table.
 enum KernelId {
-    K_CONV1_FWD, K_CONV2_FWD, K_FC1_FWD, K_FC2, K_FC2_GRAD, K_FC1_DW, K_FC1_DX, K_CONV2_DW, K_CONV2_DX, K_CONV1_DW,
-    K_CONV_REDUCE, K_APPLY_SUM, K_APPLY_SEQ, K_COUNT
+    K_CONV1_FWD, K_CONV2_FWD, K_FC1_FWD, K_FC2, K_FC1_DW, K_FC1_DX, K_CONV2_DW, K_CONV2_DX, K_CONV1_DW,
+    K_GRAD_REDUCE, K_APPLY_SUM, K_APPLY_SEQ, K_COUNT
 };
 const char* kernel_name(int id);
 

@@ -1,0 +1,115 @@
+// conv1 (1 -> 16 channels, 3x3, pad 1, on the 28x28 input) forward with fused ReLU + 2x2 max pool, and
+// its per-worker weight gradient.  K = 9 is too short for the matrix cores; both run on the vector
+// ALU with the zero-padded image in LDS.
+#include "ps_common.h"
+
+namespace ps {
+
+namespace {
+
+// conv1 (1 -> 16, 3x3, pad 1) + ReLU + 2x2 max pool.  One block per image; a thread owns one
+// pooled position and walks the 16 output channels with its 4x4 input patch in registers.
+__global__ __launch_bounds__(256) void conv1_fwd_kernel(WorkerBuffers wb)
+{
+    __shared__ float xs[30 * 30];
+    __shared__ float ws[OFF_W2];  // conv1.W (144) + conv1.b (16)
+    const int g = blockIdx.x, w = g / wb.B, t = threadIdx.x;
+    const float* theta = worker_theta(wb, w);
+    for (int i = t; i < 900; i += 256) {
+        const int yy = i / 30 - 1, xx = i % 30 - 1;
+        xs[i] = (yy >= 0 && yy < 28 && xx >= 0 && xx < 28) ? wb.x[(size_t)g * IMG_PIX + yy * 28 + xx] : 0.f;
+    }
+    if (t < OFF_W2) ws[t] = theta[OFF_W1 + t];
+    __syncthreads();
+    if (t >= P1_POS) return;
+    const int py = t / P1_W, px = t % P1_W;
+    float patch[4][4];
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) patch[a][b] = xs[(2 * py + a) * 30 + 2 * px + b];
+    for (int o = 0; o < C1; ++o) {
+        float k[9];
+#pragma unroll
+        for (int i = 0; i < 9; ++i) k[i] = ws[o * 9 + i];
+        const float bias = ws[OFF_B1 + o];
+        float v[4];
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+                float acc = bias;
+#pragma unroll
+                for (int dy = 0; dy < 3; ++dy)
+#pragma unroll
+                    for (int dx = 0; dx < 3; ++dx) acc = fmaf(k[dy * 3 + dx], patch[a + dy][b + dx], acc);
+                v[a * 2 + b] = acc;
+            }
+        int code;
+        const float best = pool_first_max(v[0], v[1], v[2], v[3], code);
+        const size_t out = (size_t)g * P1_SIZE + o * P1_POS + t;
+        wb.p1[out] = fmaxf(best, 0.f);
+        wb.am1[out] = (uint8_t)(code | (best > 0.f ? 4 : 0));
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// conv1 weight gradient: d W1[o][dy][dx] = sum over images and pooled positions of
+// dpool1g[o][p] * xpad[winner(p) + (dy,dx)].  grid (n, N_CHUNK); 16 lanes share an output channel.
+__global__ __launch_bounds__(256) void conv1_dw_kernel(WorkerBuffers wb)
+{
+    __shared__ float xs[30 * 30];
+    const int w = blockIdx.x, chunk = blockIdx.y, t = threadIdx.x, B = wb.B;
+    const int per = (B + N_CHUNK - 1) / N_CHUNK;
+    const int s0 = chunk * per, s1 = min(B, s0 + per);
+    const int o = t >> 4, l16 = t & 15;
+    float acc[9], accb = 0.f;
+#pragma unroll
+    for (int i = 0; i < 9; ++i) acc[i] = 0.f;
+    for (int s = s0; s < s1; ++s) {
+        const size_t g = (size_t)w * B + s;
+        __syncthreads();
+        for (int i = t; i < 900; i += 256) {
+            const int yy = i / 30 - 1, xx = i % 30 - 1;
+            xs[i] = (yy >= 0 && yy < 28 && xx >= 0 && xx < 28) ? wb.x[g * IMG_PIX + yy * 28 + xx] : 0.f;
+        }
+        __syncthreads();
+        for (int p = l16; p < P1_POS; p += 16) {
+            const size_t at = g * P1_SIZE + o * P1_POS + p;
+            const float v = wb.dp1g[at];
+            const int code = wb.am1[at] & 3;
+            const int base = (2 * (p / P1_W) + (code >> 1)) * 30 + 2 * (p % P1_W) + (code & 1);
+            accb += v;
+#pragma unroll
+            for (int dy = 0; dy < 3; ++dy)
+#pragma unroll
+                for (int dx = 0; dx < 3; ++dx) acc[dy * 3 + dx] = fmaf(v, xs[base + dy * 30 + dx], acc[dy * 3 + dx]);
+        }
+    }
+#pragma unroll
+    for (int m = 8; m > 0; m >>= 1) {
+#pragma unroll
+        for (int i = 0; i < 9; ++i) acc[i] += __shfl_xor(acc[i], m, 64);
+        accb += __shfl_xor(accb, m, 64);
+    }
+    if (l16 == 0) {
+        float* part = wb.part + ((size_t)w * N_PART + chunk * 4) * CONV_PART;
+#pragma unroll
+        for (int i = 0; i < 9; ++i) part[OFF_W1 + o * 9 + i] = acc[i];
+        part[OFF_B1 + o] = accb;
+    }
+}
+
+}  // namespace
+
+void launch_conv1_fwd(const WorkerBuffers& wb, hipStream_t s)
+{
+    hipLaunchKernelGGL(conv1_fwd_kernel, dim3(wb.n * wb.B), dim3(256), 0, s, wb);
+}
+
+void launch_conv1_dw(const WorkerBuffers& wb, hipStream_t s)
+{
+    hipLaunchKernelGGL(conv1_dw_kernel, dim3(wb.n, N_CHUNK), dim3(256), 0, s, wb);
+}
+
+}  // namespace ps

@@ -1,10 +1,8 @@
 // conv2 (16 -> 32 channels, 3x3, pad 1, on 14x14 maps) as implicit GEMMs on the gfx950 matrix cores
 // (v_mfma_f32_16x16x4_f32): forward with fused ReLU + 2x2 max pool, input gradient, and per-worker
-// weight gradient.  Zero-padded feature maps are staged in LDS as [channel][16][16] planes with a
-// plane pitch of 264 floats, so that
-//   - a 3x3 tap is a compile-time address offset (dy*16 + dx) from a lane's base address, and
-//   - the four lane quarters of an MFMA operand (four channels, pitch 264 = 8 mod 32) fall into
-//     disjoint LDS banks.
+// weight gradient.  Zero-padded feature maps are staged in LDS as [channel][16][16] planes (plane
+// pitch a little above 256 floats), so that a 3x3 tap is a compile-time address offset (dy*16 + dx)
+// from a lane's base address.
 // The 32x16x9 filter bank lives in registers for the whole block (72 VGPRs per lane) in exactly the
 // layout the MFMA B operand wants; it is read from the worker's ring slot once per block.
 #include "ps_common.h"
@@ -15,9 +13,12 @@ namespace {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
-constexpr int CHS = 264;            // LDS pitch of one padded 16x16 plane (floats)
-constexpr int P1_IMS = C1 * CHS;    // one image of pool1 planes: 4224 floats
-constexpr int D2_IMS = C2 * CHS;    // one image of conv2-gradient planes: 8448 floats
+// LDS pitch (floats) of one padded 16x16 plane, chosen per kernel so that the 32 lanes an LDS read
+// serves per cycle fall into 32 different banks: the lane quarters of the forward A operand are four
+// channels over 8+8 window columns (pitch = 8 mod 32), those of the input-gradient A operand two
+// channels over 16 consecutive positions (pitch = 16 mod 32), and the weight-gradient operands put 16
+// channels on 16 lanes at 2 neighbouring positions (pitch = 2 mod 32).
+constexpr int CHS_FWD = 264, CHS_DX = 272, CHS_DW = 258;
 
 __device__ __forceinline__ floatx4 mfma16(float a, float b, floatx4 c)
 {
@@ -29,8 +30,9 @@ __device__ __forceinline__ floatx4 mfma16(float a, float b, floatx4 c)
 // writes the registers into the padded LDS planes after the barrier that ends the current group.
 
 // pool1 planes of COUNT images (16 channels, 14x14 interiors); NV float4 per thread.
-template <int COUNT>
+template <int COUNT, int CHS>
 struct Pool1Stage {
+    static constexpr int P1_IMS = C1 * CHS;
     static constexpr int N4 = COUNT * (P1_SIZE / 4), NV = (N4 + 255) / 256;
     float4 v[NV];
     // images [g0, g0 + valid) exist; the rest of the group is staged as zeros
@@ -61,8 +63,9 @@ struct Pool1Stage {
 
 // Gated pool2 gradient of COUNT images, routed to the window winners of padded planes
 // d2[o][16][16] (interior at (1,1)).  clear() zeroes exactly the elements the last commit wrote.
-template <int COUNT>
+template <int COUNT, int CHS>
 struct D2Stage {
+    static constexpr int D2_IMS = C2 * CHS;
     static constexpr int N = COUNT * P2_SIZE, NV = (N + 255) / 256;
     float v[NV];
     uint8_t code[NV];
@@ -105,6 +108,7 @@ constexpr int FWD_G = 4, FWD_IPB = 16;
 
 __global__ __launch_bounds__(256, 2) void conv2_fwd_kernel(WorkerBuffers wb, int blocks_per_worker)
 {
+    constexpr int CHS = CHS_FWD, P1_IMS = C1 * CHS;
     __shared__ __attribute__((aligned(16))) float tile[FWD_G * P1_IMS];  // 67,584 B
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, q = lane >> 4, l16 = lane & 15;
     const int w = blockIdx.x / blocks_per_worker, chunk = blockIdx.x % blocks_per_worker;
@@ -123,7 +127,7 @@ __global__ __launch_bounds__(256, 2) void conv2_fwd_kernel(WorkerBuffers wb, int
         reinterpret_cast<float4*>(tile)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
     __syncthreads();
 
-    Pool1Stage<FWD_G> stage;
+    Pool1Stage<FWD_G, CHS> stage;
     stage.prefetch(wb.p1, (size_t)w * B + s_begin, min(FWD_G, s_end - s_begin), tid);
     int rot = 0;
     for (int s0 = s_begin; s0 < s_end; s0 += FWD_G, ++rot) {
@@ -170,7 +174,8 @@ constexpr int DX_G = 2, DX_IPB = 16;
 
 __global__ __launch_bounds__(256, 2) void conv2_dx_kernel(WorkerBuffers wb, int blocks_per_worker)
 {
-    __shared__ __attribute__((aligned(16))) float tile[DX_G * D2_IMS];  // 67,584 B
+    constexpr int CHS = CHS_DX, D2_IMS = C2 * CHS;
+    __shared__ __attribute__((aligned(16))) float tile[DX_G * D2_IMS];  // 69,632 B
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, q = lane >> 4, l16 = lane & 15;
     const int w = blockIdx.x / blocks_per_worker, chunk = blockIdx.x % blocks_per_worker;
     const int B = wb.B, s_begin = chunk * DX_IPB, s_end = min(B, s_begin + DX_IPB);
@@ -186,7 +191,7 @@ __global__ __launch_bounds__(256, 2) void conv2_dx_kernel(WorkerBuffers wb, int 
         reinterpret_cast<float4*>(tile)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
     __syncthreads();
 
-    D2Stage<DX_G> stage;
+    D2Stage<DX_G, CHS> stage;
     stage.prefetch(wb, (size_t)w * B + s_begin, min(DX_G, s_end - s_begin), tid);
     int rot = 0;
     for (int s0 = s_begin; s0 < s_end; s0 += DX_G, ++rot) {
@@ -231,8 +236,9 @@ __global__ __launch_bounds__(256, 2) void conv2_dx_kernel(WorkerBuffers wb, int 
 // their 18 accumulator tiles across images; each wavefront's sum goes to its own partial slot.
 __global__ __launch_bounds__(256, 2) void conv2_dw_kernel(WorkerBuffers wb)
 {
-    __shared__ __attribute__((aligned(16))) float d2[D2_IMS];   // 33,792 B
-    __shared__ __attribute__((aligned(16))) float p1t[P1_IMS];  // 16,896 B
+    constexpr int CHS = CHS_DW, D2_IMS = C2 * CHS, P1_IMS = C1 * CHS;
+    __shared__ __attribute__((aligned(16))) float d2[D2_IMS];   // 33,024 B
+    __shared__ __attribute__((aligned(16))) float p1t[P1_IMS];  // 16,512 B
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, q = lane >> 4, l16 = lane & 15;
     const int w = blockIdx.x, chunk = blockIdx.y, B = wb.B;
     const int per = (B + N_CHUNK - 1) / N_CHUNK;
@@ -249,8 +255,8 @@ __global__ __launch_bounds__(256, 2) void conv2_dw_kernel(WorkerBuffers wb)
     for (int i = tid; i < P1_IMS / 4; i += 256) reinterpret_cast<float4*>(p1t)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
     __syncthreads();
 
-    D2Stage<1> sd;
-    Pool1Stage<1> sp;
+    D2Stage<1, CHS> sd;
+    Pool1Stage<1, CHS> sp;
     if (s_begin < s_end) {
         sd.prefetch(wb, (size_t)w * B + s_begin, 1, tid);
         sp.prefetch(wb.p1, (size_t)w * B + s_begin, 1, tid);

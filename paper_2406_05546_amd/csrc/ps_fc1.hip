@@ -1,0 +1,94 @@
+// The three contractions of the 1568 -> 512 fully connected layer on the matrix cores: forward with
+// fused bias + ReLU + dropout, input gradient with the conv2 ReLU gate, and the per-worker weight
+// gradient written straight into the worker's queue entry.
+#include "ps_common.h"
+#include "ps_gemm.h"
+#include "ps_philox.h"
+
+namespace ps {
+
+namespace {
+
+// fc1 on the matrix cores.  Rows m are fc1 units, columns n are the worker's samples, so that the
+// four accumulators a lane holds for one column are four consecutive units of one sample: exactly
+// the four words of one Philox call.
+struct Fc1FwdEpi {
+    WorkerBuffers wb;
+    __device__ const float* a_ptr(int z) const { return worker_theta(wb, z) + OFF_W3; }
+    __device__ const float* b_ptr(int z) const { return wb.p2 + (size_t)z * wb.B * P2_SIZE; }
+    __device__ void operator()(int z, int m, int n, float4 acc) const
+    {
+        const float4 b = *reinterpret_cast<const float4*>(worker_theta(wb, z) + OFF_B3 + m);
+        const WorkerMeta mt = wb.meta[z];
+        const uint4 r = philox4x32_10(make_uint4(mt.mb_lo, mt.mb_hi, (uint32_t)n, (uint32_t)(m >> 2)),
+                                      make_uint2(wb.seed_lo, wb.seed_hi));
+        float4 o;
+        o.x = r.x >= wb.drop_threshold ? fmaxf(acc.x + b.x, 0.f) * wb.drop_scale : 0.f;
+        o.y = r.y >= wb.drop_threshold ? fmaxf(acc.y + b.y, 0.f) * wb.drop_scale : 0.f;
+        o.z = r.z >= wb.drop_threshold ? fmaxf(acc.z + b.z, 0.f) * wb.drop_scale : 0.f;
+        o.w = r.w >= wb.drop_threshold ? fmaxf(acc.w + b.w, 0.f) * wb.drop_scale : 0.f;
+        *reinterpret_cast<float4*>(wb.ht + ((size_t)z * wb.B + n) * FC1 + m) = o;
+    }
+};
+
+// d pool2 = d3 . W3, zeroed where the pooled activation is zero (ReLU gate of conv2).
+// Rows m are pool2 features, columns n samples, contraction over the 512 units.
+struct Fc1DxEpi {
+    WorkerBuffers wb;
+    __device__ const float* a_ptr(int z) const { return worker_theta(wb, z) + OFF_W3; }
+    __device__ const float* b_ptr(int z) const { return wb.d3 + (size_t)z * wb.B * FC1; }
+    __device__ void operator()(int z, int m, int n, float4 acc) const
+    {
+        const size_t at = ((size_t)z * wb.B + n) * P2_SIZE + m;
+        const float4 a = *reinterpret_cast<const float4*>(wb.p2 + at);
+        float4 o;
+        o.x = a.x > 0.f ? acc.x : 0.f;
+        o.y = a.y > 0.f ? acc.y : 0.f;
+        o.z = a.z > 0.f ? acc.z : 0.f;
+        o.w = a.w > 0.f ? acc.w : 0.f;
+        *reinterpret_cast<float4*>(wb.dp2g + at) = o;
+    }
+};
+
+// Per-worker d fc1.W[u][i] = sum_s d3[s][u] * pool2[s][i], written into the worker's queue entry.
+// Rows m are units, columns n features, so a wavefront's lanes run along contiguous memory.
+struct Fc1DwEpi {
+    WorkerBuffers wb;
+    __device__ const float* a_ptr(int z) const { return wb.d3 + (size_t)z * wb.B * FC1; }
+    __device__ const float* b_ptr(int z) const { return wb.p2 + (size_t)z * wb.B * P2_SIZE; }
+    __device__ void operator()(int z, int m, int n, float4 acc) const
+    {
+        float* g = worker_grad(wb, z) + OFF_W3 + (size_t)m * P2_SIZE + n;
+        g[0] = acc.x;
+        g[P2_SIZE] = acc.y;
+        g[2 * P2_SIZE] = acc.z;
+        g[3 * P2_SIZE] = acc.w;
+    }
+};
+
+inline dim3 gemm_grid(int M, int N, int n) { return dim3((M + GEMM_BM - 1) / GEMM_BM, (N + GEMM_BN - 1) / GEMM_BN, n); }
+
+}  // namespace
+
+void launch_fc1_fwd(const WorkerBuffers& wb, hipStream_t s)
+{
+    GemmShape sh{FC1, wb.B, P2_SIZE, P2_SIZE, P2_SIZE};
+    hipLaunchKernelGGL((gemm_f32_mfma<true, true, Fc1FwdEpi>), gemm_grid(sh.M, sh.N, wb.n), dim3(256), 0, s, sh,
+                       Fc1FwdEpi{wb});
+}
+
+void launch_fc1_dw(const WorkerBuffers& wb, hipStream_t s)
+{
+    GemmShape dw{FC1, P2_SIZE, wb.B, FC1, P2_SIZE};
+    hipLaunchKernelGGL((gemm_f32_mfma<false, false, Fc1DwEpi>), gemm_grid(dw.M, dw.N, wb.n), dim3(256), 0, s, dw,
+                       Fc1DwEpi{wb});
+}
+
+void launch_fc1_dx(const WorkerBuffers& wb, hipStream_t s)
+{
+    GemmShape dx{P2_SIZE, wb.B, FC1, P2_SIZE, FC1};
+    hipLaunchKernelGGL((gemm_f32_mfma<false, true, Fc1DxEpi>), gemm_grid(dx.M, dx.N, wb.n), dim3(256), 0, s, dx,
+                       Fc1DxEpi{wb});
+}
+
+}  // namespace ps

@@ -1,0 +1,121 @@
+// fc2 (512 -> 10), softmax cross-entropy and everything of their backward pass that does not need
+// the matrix cores, in one kernel:
+//   z = W4 . h + b4;  loss_i = logsumexp(z) - z[y];  d4 = (softmax(z) - onehot(y)) / B;
+//   d3 = (W4^T d4) / (1-p) where the dropped-and-rectified fc1 activation is > 0, else 0;
+//   per worker: d W4 += d4 (x) h,  d b4 += d4,  d b3 += d3,  loss += loss_i.
+// A wavefront keeps its 10 x 8 slice of W4 and of the d W4 accumulator in registers and walks every
+// (4 * split)-th image of one worker; lane l owns fc1 units l, l+64, ..., l+448.  Each wavefront's
+// sums go to its own partial slot and are added up in fixed order by the reduction kernel.
+#include "ps_common.h"
+
+namespace ps {
+
+namespace {
+
+__global__ __launch_bounds__(256) void fc2_kernel(WorkerBuffers wb)
+{
+    const int lane = threadIdx.x & 63, w = blockIdx.x, B = wb.B;
+    const int nsub = 4 * gridDim.y, sub = 4 * blockIdx.y + (threadIdx.x >> 6);
+    const float* __restrict__ theta = worker_theta(wb, w);
+    float w4[NCLS][8], acc[NCLS][8], accb3[8], accb4[NCLS], b4[NCLS];
+#pragma unroll
+    for (int c = 0; c < NCLS; ++c) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            w4[c][j] = theta[OFF_W4 + c * FC1 + lane + 64 * j];
+            acc[c][j] = 0.f;
+        }
+        accb4[c] = 0.f;
+        b4[c] = theta[OFF_B4 + c];
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) accb3[j] = 0.f;
+    float loss = 0.f;
+    const float inv_b = 1.f / (float)B;
+
+    float hn[8];
+    if (sub < B) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) hn[j] = wb.ht[((size_t)w * B + sub) * FC1 + lane + 64 * j];
+    }
+    for (int s = sub; s < B; s += nsub) {
+        const size_t g = (size_t)w * B + s;
+        float hv[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) hv[j] = hn[j];
+        if (s + nsub < B) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) hn[j] = wb.ht[(g + nsub) * FC1 + lane + 64 * j];
+        }
+        float z[NCLS];
+#pragma unroll
+        for (int c = 0; c < NCLS; ++c) {
+            float part = 0.f;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) part = fmaf(hv[j], w4[c][j], part);
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off, 64);
+            z[c] = part + b4[c];
+        }
+        const int label = wb.y[g];
+        float zmax = z[0];
+        int pred = 0;
+#pragma unroll
+        for (int c = 1; c < NCLS; ++c)
+            if (z[c] > zmax) { zmax = z[c]; pred = c; }
+        float se = 0.f;
+#pragma unroll
+        for (int c = 0; c < NCLS; ++c) se += expf(z[c] - zmax);
+        const float lse = zmax + logf(se);
+        float d4[NCLS], zy = 0.f;
+#pragma unroll
+        for (int c = 0; c < NCLS; ++c) {
+            d4[c] = (expf(z[c] - lse) - (c == label ? 1.f : 0.f)) * inv_b;
+            if (c == label) zy = z[c];
+            accb4[c] += d4[c];
+        }
+        loss += lse - zy;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            float dh = 0.f;
+#pragma unroll
+            for (int c = 0; c < NCLS; ++c) {
+                dh = fmaf(d4[c], w4[c][j], dh);
+                acc[c][j] = fmaf(d4[c], hv[j], acc[c][j]);
+            }
+            const float d3 = hv[j] > 0.f ? dh * wb.drop_scale : 0.f;
+            wb.d3[g * FC1 + lane + 64 * j] = d3;
+            accb3[j] += d3;
+        }
+        float zl = 0.f;
+#pragma unroll
+        for (int c = 0; c < NCLS; ++c)
+            if (lane == c) zl = z[c];
+        if (lane < NCLS) wb.z[g * NCLS + lane] = zl;
+        if (lane == 0) wb.pred[g] = pred;
+    }
+
+    float* part = wb.fpart + ((size_t)w * nsub + sub) * FC2_PART;
+#pragma unroll
+    for (int c = 0; c < NCLS; ++c)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) part[c * FC1 + lane + 64 * j] = acc[c][j];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) part[FC2_PART_B3 + lane + 64 * j] = accb3[j];
+    if (lane == 0) {
+#pragma unroll
+        for (int c = 0; c < NCLS; ++c) part[FC2_PART_B4 + c] = accb4[c];
+        part[FC2_PART_LOSS] = loss;
+    }
+}
+
+}  // namespace
+
+int fc2_split(int n) { return std::min(16, std::max(1, (512 + n - 1) / n)); }
+
+void launch_fc2(const WorkerBuffers& wb, hipStream_t s)
+{
+    hipLaunchKernelGGL(fc2_kernel, dim3(wb.n, fc2_split(wb.n)), dim3(256), 0, s, wb);
+}
+
+}  // namespace ps
