@@ -45,7 +45,7 @@ struct Carve {
 };
 
 struct Layout {
-    uint64_t theta, ring, queue, meta, idx, p1, am1, p2, am2, ht, z, pred, d3, dp2g, dp1g, part, fpart, keep, total;
+    uint64_t theta, ring, queue, meta, idx, p1, am1, p2, am2, ht, z, pred, d3, dp2g, part, part1, fpart, keep, total;
 };
 
 bool config_ok(const ps_config* c)
@@ -73,8 +73,8 @@ Layout make_layout(const ps_config& c)
     l.pred = k.take(n * 4);
     l.d3 = k.take(n * FC1 * 4);
     l.dp2g = k.take(n * P2_SIZE * 4);
-    l.dp1g = k.take(n * P1_SIZE * 4);
     l.part = k.take((uint64_t)c.max_workers * N_PART * CONV_PART * 4);
+    l.part1 = k.take((uint64_t)c.max_workers * conv1_part_slots(c.batch) * OFF_W2 * 4);
     l.fpart = k.take((uint64_t)4 * (512 + c.max_workers) * FC2_PART * 4);  // >= n * 4 * fc2_split(n) slots
     l.keep = k.take((uint64_t)c.batch * FC1);
     l.total = k.off;
@@ -189,8 +189,8 @@ WorkerBuffers buffers(const ps_ctx* c, int n, const float* x, const int32_t* y, 
     wb.pred = c->at<int32_t>(c->lay.pred);
     wb.d3 = c->at<float>(c->lay.d3);
     wb.dp2g = c->at<float>(c->lay.dp2g);
-    wb.dp1g = c->at<float>(c->lay.dp1g);
     wb.part = c->at<float>(c->lay.part);
+    wb.part1 = c->at<float>(c->lay.part1);
     wb.fpart = c->at<float>(c->lay.fpart);
     wb.loss = loss;
     wb.n = n;

@@ -47,8 +47,8 @@ struct WorkerBuffers {
     int32_t* pred;       // [n*B]
     float* d3;           // [n*B][512]      d loss / d fc1 pre-activation
     float* dp2g;         // [n*B][1568]     d loss / d pool2, zero where pool2 == 0
-    float* dp1g;         // [n*B][3136]     d loss / d pool1, zero where pool1 == 0
-    float* part;         // [n][N_PART][4800] partial sums of conv1/conv2 weight gradients
+    float* part;         // [n][N_PART][4800] partial sums of the conv2 weight gradient (conv1 region unused)
+    float* part1;        // [n][conv1_part_slots(B)][160] partial sums of the conv1 weight gradient
     float* fpart;        // [n][4*split][FC2_PART] partial sums of the fc2 kernel's wavefronts
     float* loss;         // [n] or nullptr
     int32_t n, B;
@@ -83,9 +83,9 @@ __device__ __forceinline__ float pool_first_max(float v0, float v1, float v2, fl
 constexpr int FC2_PART_B4 = NCLS * FC1, FC2_PART_B3 = FC2_PART_B4 + NCLS, FC2_PART_LOSS = FC2_PART_B3 + FC1,
               FC2_PART = 5648;
 int fc2_split(int n);  // blocks per worker of the fc2 kernel (4 partial slots each)
+int conv1_part_slots(int batch);  // conv1 partial slots per worker (one per wavefront of conv2's input-gradient kernel)
 
 void launch_conv1_fwd(const WorkerBuffers& wb, hipStream_t s);
-void launch_conv1_dw(const WorkerBuffers& wb, hipStream_t s);
 void launch_fc1_fwd(const WorkerBuffers& wb, hipStream_t s);
 void launch_fc1_dw(const WorkerBuffers& wb, hipStream_t s);
 void launch_fc1_dx(const WorkerBuffers& wb, hipStream_t s);
@@ -96,7 +96,7 @@ void launch_conv2_dw(const WorkerBuffers& wb, hipStream_t s);
 
 // Kernels of the path, in launch order; ids index the per-kernel timing table.
 enum KernelId {
-    K_CONV1_FWD, K_CONV2_FWD, K_FC1_FWD, K_FC2, K_FC1_DW, K_FC1_DX, K_CONV2_DW, K_CONV2_DX, K_CONV1_DW,
+    K_CONV1_FWD, K_CONV2_FWD, K_FC1_FWD, K_FC2, K_FC1_DW, K_FC1_DX, K_CONV2_DW, K_CONV2_DX,
     K_GRAD_REDUCE, K_APPLY_SUM, K_APPLY_SEQ, K_COUNT
 };
 const char* kernel_name(int id);

@@ -1,6 +1,6 @@
-// conv1 (1 -> 16 channels, 3x3, pad 1, on the 28x28 input) forward with fused ReLU + 2x2 max pool, and
-// its per-worker weight gradient.  K = 9 is too short for the matrix cores; both run on the vector
-// ALU with the zero-padded image in LDS.
+// conv1 (1 -> 16 channels, 3x3, pad 1, on the 28x28 input) forward with fused ReLU + 2x2 max pool.
+// K = 9 is too short for the matrix cores; it runs on the vector ALU with the zero-padded image in
+// LDS.  (Its weight gradient is fused into conv2's input-gradient kernel.)
 #include "ps_common.h"
 
 namespace ps {
@@ -53,63 +53,11 @@ __global__ __launch_bounds__(256) void conv1_fwd_kernel(WorkerBuffers wb)
     }
 }
 
-// ---------------------------------------------------------------------------------------------
-// conv1 weight gradient: d W1[o][dy][dx] = sum over images and pooled positions of
-// dpool1g[o][p] * xpad[winner(p) + (dy,dx)].  grid (n, N_CHUNK); 16 lanes share an output channel.
-__global__ __launch_bounds__(256) void conv1_dw_kernel(WorkerBuffers wb)
-{
-    __shared__ float xs[30 * 30];
-    const int w = blockIdx.x, chunk = blockIdx.y, t = threadIdx.x, B = wb.B;
-    const int per = (B + N_CHUNK - 1) / N_CHUNK;
-    const int s0 = chunk * per, s1 = min(B, s0 + per);
-    const int o = t >> 4, l16 = t & 15;
-    float acc[9], accb = 0.f;
-#pragma unroll
-    for (int i = 0; i < 9; ++i) acc[i] = 0.f;
-    for (int s = s0; s < s1; ++s) {
-        const size_t g = (size_t)w * B + s;
-        __syncthreads();
-        for (int i = t; i < 900; i += 256) {
-            const int yy = i / 30 - 1, xx = i % 30 - 1;
-            xs[i] = (yy >= 0 && yy < 28 && xx >= 0 && xx < 28) ? wb.x[g * IMG_PIX + yy * 28 + xx] : 0.f;
-        }
-        __syncthreads();
-        for (int p = l16; p < P1_POS; p += 16) {
-            const size_t at = g * P1_SIZE + o * P1_POS + p;
-            const float v = wb.dp1g[at];
-            const int code = wb.am1[at] & 3;
-            const int base = (2 * (p / P1_W) + (code >> 1)) * 30 + 2 * (p % P1_W) + (code & 1);
-            accb += v;
-#pragma unroll
-            for (int dy = 0; dy < 3; ++dy)
-#pragma unroll
-                for (int dx = 0; dx < 3; ++dx) acc[dy * 3 + dx] = fmaf(v, xs[base + dy * 30 + dx], acc[dy * 3 + dx]);
-        }
-    }
-#pragma unroll
-    for (int m = 8; m > 0; m >>= 1) {
-#pragma unroll
-        for (int i = 0; i < 9; ++i) acc[i] += __shfl_xor(acc[i], m, 64);
-        accb += __shfl_xor(accb, m, 64);
-    }
-    if (l16 == 0) {
-        float* part = wb.part + ((size_t)w * N_PART + chunk * 4) * CONV_PART;
-#pragma unroll
-        for (int i = 0; i < 9; ++i) part[OFF_W1 + o * 9 + i] = acc[i];
-        part[OFF_B1 + o] = accb;
-    }
-}
-
 }  // namespace
 
 void launch_conv1_fwd(const WorkerBuffers& wb, hipStream_t s)
 {
     hipLaunchKernelGGL(conv1_fwd_kernel, dim3(wb.n * wb.B), dim3(256), 0, s, wb);
-}
-
-void launch_conv1_dw(const WorkerBuffers& wb, hipStream_t s)
-{
-    hipLaunchKernelGGL(conv1_dw_kernel, dim3(wb.n, N_CHUNK), dim3(256), 0, s, wb);
 }
 
 }  // namespace ps

@@ -166,16 +166,22 @@ __global__ __launch_bounds__(256, 2) void conv2_fwd_kernel(WorkerBuffers wb, int
 }
 
 // ---------------------------------------------------------------------------------------------
-// Input gradient: d pool1[c][y][x] = sum_{o,dy,dx} d2pad[o][y+2-dy][x+2-dx] * W2[o][c][dy][dx], zeroed
-// where pool1 == 0.  GEMM rows are the 196 positions of an image (16 per tile), columns the 16 input
-// channels, K = (flipped tap, output channel) = 288.  A block owns up to DX_IPB images of one worker
-// and walks them DX_G at a time.
+// Input gradient of conv2 fused with the weight gradient of conv1.
+//   d pool1[c][y][x] = sum_{o,dy,dx} d2pad[o][y+2-dy][x+2-dx] * W2[o][c][dy][dx], zeroed where pool1 == 0.
+// GEMM rows are the 196 positions of an image (16 per tile), columns the 16 input channels,
+// K = (flipped tap, output channel) = 288.  The result never goes to memory: conv1 has no input
+// gradient, so each value is routed to its pool1 window's winner and multiplied right away with the
+// 3x3 neighbourhood of input pixels there,
+//   d W1[c][dy][dx] += d pool1[c][p] * xpad[winner(c,p) + (dy,dx)],   d b1[c] += d pool1[c][p],
+// on the vector ALU, which is idle while the matrix cores run.  A block owns up to DX_IPB images of
+// one worker and walks them DX_G at a time; each wavefront's conv1 sums go to its own partial slot.
 constexpr int DX_G = 2, DX_IPB = 16;
 
 __global__ __launch_bounds__(256, 2) void conv2_dx_kernel(WorkerBuffers wb, int blocks_per_worker)
 {
     constexpr int CHS = CHS_DX, D2_IMS = C2 * CHS;
     __shared__ __attribute__((aligned(16))) float tile[DX_G * D2_IMS];  // 69,632 B
+    __shared__ __attribute__((aligned(16))) float xs[DX_G * 900];       // zero-padded 30x30 input images
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, q = lane >> 4, l16 = lane & 15;
     const int w = blockIdx.x / blocks_per_worker, chunk = blockIdx.x % blocks_per_worker;
     const int B = wb.B, s_begin = chunk * DX_IPB, s_end = min(B, s_begin + DX_IPB);
@@ -189,18 +195,57 @@ __global__ __launch_bounds__(256, 2) void conv2_dx_kernel(WorkerBuffers wb, int 
 
     for (int i = tid; i < DX_G * D2_IMS / 4; i += 256)
         reinterpret_cast<float4*>(tile)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int i = tid; i < DX_G * 900; i += 256) xs[i] = 0.f;
     __syncthreads();
+
+    // input pixels of a group: DX_G * 196 float4, at most two per thread
+    constexpr int NX4 = DX_G * (IMG_PIX / 4);
+    float4 xv[2];
+    auto prefetch_x = [&](size_t g0, int valid) {
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const int i4 = tid + 256 * k;
+            xv[k] = (i4 < NX4 && i4 / (IMG_PIX / 4) < valid)
+                        ? *reinterpret_cast<const float4*>(wb.x + g0 * IMG_PIX + (size_t)i4 * 4)
+                        : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    };
+    auto commit_x = [&]() {
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const int i4 = tid + 256 * k;
+            if (i4 >= NX4) break;
+            const int img = i4 / (IMG_PIX / 4), r = (i4 % (IMG_PIX / 4)) * 4;  // 28 % 4 == 0: one image row
+            float* dst = xs + img * 900 + (r / IMG_W + 1) * 30 + r % IMG_W + 1;
+            dst[0] = xv[k].x; dst[1] = xv[k].y; dst[2] = xv[k].z; dst[3] = xv[k].w;
+        }
+    };
+
+    float g1[9], gb1 = 0.f;  // this lane's share of d W1[l16][.] and d b1[l16]
+#pragma unroll
+    for (int i = 0; i < 9; ++i) g1[i] = 0.f;
 
     D2Stage<DX_G, CHS> stage;
     stage.prefetch(wb, (size_t)w * B + s_begin, min(DX_G, s_end - s_begin), tid);
+    prefetch_x((size_t)w * B + s_begin, min(DX_G, s_end - s_begin));
     int rot = 0;
     for (int s0 = s_begin; s0 < s_end; s0 += DX_G, ++rot) {
         const size_t g0 = (size_t)w * B + s0;
         const int valid = min(DX_G, s_end - s0);
         stage.commit(tile, tid);
+        commit_x();
         __syncthreads();
-        if (s0 + DX_G < s_end) stage.prefetch(wb, g0 + DX_G, min(DX_G, s_end - s0 - DX_G), tid);
+        if (s0 + DX_G < s_end) {
+            stage.prefetch(wb, g0 + DX_G, min(DX_G, s_end - s0 - DX_G), tid);
+            prefetch_x(g0 + DX_G, min(DX_G, s_end - s0 - DX_G));
+        }
         for (int t = (wave + rot) & 3; t < (DX_G * P1_POS + 15) / 16; t += 4) {
+            // lane (q, l16) will hold channel l16 at positions 16t + 4q .. +3 (never straddling an image);
+            // fetch their pool1 window bytes (winner, gate) before the matrix work
+            const int mo = 16 * t + 4 * q, img_o = mo / P1_POS, pos_o = mo % P1_POS;
+            const bool live = mo < DX_G * P1_POS && img_o < valid;
+            uint32_t win = 0;
+            if (live) win = *reinterpret_cast<const uint32_t*>(wb.am1 + (g0 + img_o) * P1_SIZE + l16 * P1_POS + pos_o);
             // A operand: lane row l16 = position 16t + l16 of the group (reads of a row beyond the group
             // are redirected to position 0 and their results dropped)
             const int m = 16 * t + l16, mm = m < DX_G * P1_POS ? m : 0;
@@ -210,21 +255,39 @@ __global__ __launch_bounds__(256, 2) void conv2_dx_kernel(WorkerBuffers wb, int 
 #pragma unroll
             for (int s = 0; s < 72; ++s)
                 acc = mfma16(a[4 * (s & 7) * CHS + ((s >> 3) / 3) * 16 + (s >> 3) % 3], wreg[s], acc);
-            // lane (q, l16) holds channel l16 at positions 16t + 4q .. +3 (never straddling an image)
-            const int mo = 16 * t + 4 * q, img_o = mo / P1_POS, pos_o = mo % P1_POS;
-            if (mo < DX_G * P1_POS && img_o < valid) {
-                const size_t at = (g0 + img_o) * P1_SIZE + l16 * P1_POS + pos_o;
-                const uint32_t gate = *reinterpret_cast<const uint32_t*>(wb.am1 + at);
-                float4 o;
-                o.x = (gate & 0x00000004u) ? acc[0] : 0.f;
-                o.y = (gate & 0x00000400u) ? acc[1] : 0.f;
-                o.z = (gate & 0x00040000u) ? acc[2] : 0.f;
-                o.w = (gate & 0x04000000u) ? acc[3] : 0.f;
-                *reinterpret_cast<float4*>(wb.dp1g + at) = o;
+            if (live) {
+                const float* ximg = xs + img_o * 900;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t b = win >> (8 * i);
+                    const float v = (b & 4u) ? acc[i] : 0.f;
+                    const int p = pos_o + i;
+                    const float* px = ximg + (2 * (p / P1_W) + ((b >> 1) & 1)) * 30 + 2 * (p % P1_W) + (b & 1);
+                    gb1 += v;
+#pragma unroll
+                    for (int dy = 0; dy < 3; ++dy)
+#pragma unroll
+                        for (int dx = 0; dx < 3; ++dx) g1[dy * 3 + dx] = fmaf(v, px[dy * 30 + dx], g1[dy * 3 + dx]);
+                }
             }
         }
         __syncthreads();
         stage.clear(tile, tid);  // the same thread rewrites these windows at the next commit
+    }
+
+    // fold the four lane quarters; lanes of quarter 0 hold the wavefront's sums for channel l16
+#pragma unroll
+    for (int i = 0; i < 9; ++i) {
+        g1[i] += __shfl_xor(g1[i], 16, 64);
+        g1[i] += __shfl_xor(g1[i], 32, 64);
+    }
+    gb1 += __shfl_xor(gb1, 16, 64);
+    gb1 += __shfl_xor(gb1, 32, 64);
+    if (q == 0) {
+        float* part = wb.part1 + ((size_t)w * blocks_per_worker * 4 + chunk * 4 + wave) * OFF_W2;
+#pragma unroll
+        for (int i = 0; i < 9; ++i) part[OFF_W1 + l16 * 9 + i] = g1[i];
+        part[OFF_B1 + l16] = gb1;
     }
 }
 
@@ -313,6 +376,8 @@ void launch_conv2_fwd(const WorkerBuffers& wb, hipStream_t s)
     const int bpw = (wb.B + FWD_IPB - 1) / FWD_IPB;
     hipLaunchKernelGGL(conv2_fwd_kernel, dim3(wb.n * bpw), dim3(256), 0, s, wb, bpw);
 }
+
+int conv1_part_slots(int batch) { return 4 * ((batch + DX_IPB - 1) / DX_IPB); }
 
 void launch_conv2_dx(const WorkerBuffers& wb, hipStream_t s)
 {

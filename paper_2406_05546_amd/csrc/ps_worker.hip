@@ -12,9 +12,9 @@ namespace ps {
 namespace {
 
 // Sums the partial slots in fixed order into the worker's queue entry: conv1 tensors have one partial
-// per chunk (slot 4*chunk), conv2 tensors one per (chunk, wavefront), fc2 tensors, fc1 bias and the
-// loss one per wavefront of the fc2 kernel.
-__global__ __launch_bounds__(256) void grad_reduce_kernel(WorkerBuffers wb, int fc2_slots)
+// per wavefront of conv2's input-gradient kernel, conv2 tensors one per (chunk, wavefront) of its
+// weight-gradient kernel, fc2 tensors, fc1 bias and the loss one per wavefront of the fc2 kernel.
+__global__ __launch_bounds__(256) void grad_reduce_kernel(WorkerBuffers wb, int fc2_slots, int c1_slots)
 {
     const int w = blockIdx.x;
     float* grad = worker_grad(wb, w);
@@ -23,8 +23,8 @@ __global__ __launch_bounds__(256) void grad_reduce_kernel(WorkerBuffers wb, int 
     for (int i = tid; i < CONV_PART; i += stride) {
         float sum = 0.f;
         if (i < OFF_W2) {
-#pragma unroll
-            for (int c = 0; c < N_CHUNK; ++c) sum += part[(size_t)c * 4 * CONV_PART + i];
+            const float* p1 = wb.part1 + (size_t)w * c1_slots * OFF_W2 + i;
+            for (int c = 0; c < c1_slots; ++c) sum += p1[(size_t)c * OFF_W2];
         } else {
 #pragma unroll
             for (int c = 0; c < N_PART; ++c) sum += part[(size_t)c * CONV_PART + i];
@@ -86,8 +86,8 @@ hipError_t launch_worker_backward(const WorkerBuffers& wb, hipStream_t s, Profil
     PS_TIMED(K_FC1_DX, launch_fc1_dx(wb, s));
     PS_TIMED(K_CONV2_DW, launch_conv2_dw(wb, s));
     PS_TIMED(K_CONV2_DX, launch_conv2_dx(wb, s));
-    PS_TIMED(K_CONV1_DW, launch_conv1_dw(wb, s));
-    PS_TIMED(K_GRAD_REDUCE, hipLaunchKernelGGL(grad_reduce_kernel, dim3(wb.n, 8), dim3(256), 0, s, wb, 4 * fc2_split(wb.n)));
+    PS_TIMED(K_GRAD_REDUCE, hipLaunchKernelGGL(grad_reduce_kernel, dim3(wb.n, 8), dim3(256), 0, s, wb, 4 * fc2_split(wb.n),
+                                                conv1_part_slots(wb.B)));
     return hipGetLastError();
 }
 
@@ -96,7 +96,7 @@ const char* kernel_name(int id)
     static const char* const names[K_COUNT] = {
         "conv1_fwd_kernel", "conv2_fwd_kernel", "gemm_f32_mfma<true, true, Fc1FwdEpi>", "fc2_kernel",
         "gemm_f32_mfma<false, false, Fc1DwEpi>", "gemm_f32_mfma<false, true, Fc1DxEpi>", "conv2_dw_kernel",
-        "conv2_dx_kernel", "conv1_dw_kernel", "grad_reduce_kernel", "apply_kernel<0>", "apply_kernel<1>"};
+        "conv2_dx_kernel", "grad_reduce_kernel", "apply_kernel<0>", "apply_kernel<1>"};
     return id >= 0 && id < K_COUNT ? names[id] : "";
 }
 

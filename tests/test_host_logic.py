@@ -41,7 +41,7 @@ def test_workspace_bytes_and_argument_checks_without_a_gpu():
     assert lib.ps_sync(None) == ps.PS_EINVAL and lib.ps_destroy(None) == ps.PS_EINVAL
     assert lib.ps_last_error(None) == b""
     names = [lib.ps_profile_kernel_name(k).decode() for k in range(lib.ps_profile_kernel_count())]
-    assert len(names) == 12 and len(set(names)) == 12 and lib.ps_profile_kernel_name(99) == b""
+    assert len(names) == 11 and len(set(names)) == 11 and lib.ps_profile_kernel_name(99) == b""
 
 
 def test_minibatches_depend_only_on_logical_ids():
