@@ -31,9 +31,9 @@ FLOP_PER_IMAGE = 10718208
 
 # algorithmic FLOP per image of each worker kernel (2 x multiply-accumulates of the layer it computes)
 KERNEL_FLOP_PER_IMAGE = {
-    "conv1_fwd_kernel": 225792, "conv2_fwd_kernel": 1806336, "gemm_f32_mfma<true, true, Fc1FwdEpi>": 1605632,
-    "fc2_kernel": 30720, "gemm_f32_mfma<false, false, Fc1DwEpi>": 1605632,
-    "gemm_f32_mfma<false, true, Fc1DxEpi>": 1605632, "conv2_dw_kernel": 1806336,
+    "conv1_fwd_kernel": 225792, "conv2_fwd_kernel": 1806336, "gemm_f32_mfma<Fc1FwdEpi>": 1605632,
+    "fc2_kernel": 30720, "gemm_f32_mfma<Fc1DwEpi>": 1605632,
+    "gemm_f32_mfma<Fc1DxEpi>": 1605632, "conv2_dw_kernel": 1806336,
     "conv2_dx_kernel": 1806336 + 225792,   # conv2 input gradient + fused conv1 weight gradient
     "grad_reduce_kernel": 0,
 }

@@ -168,7 +168,7 @@ PS_API ps_status ps_debug_last_batch(ps_ctx* ctx, int32_t i, uint8_t* pool1_host
  * for the stream, clears the totals and switches timing on (enable != 0) or off.  ps_profile_read
  * waits for the stream and reports the summed duration and number of launches of kernel
  * `kernel_id` in [0, ps_profile_kernel_count()); ps_profile_kernel_name gives the kernel's function
- * name as a profiler prints it ("" for an unknown id). */
+ * name, template arguments abbreviated to the distinguishing one ("" for an unknown id). */
 PS_API ps_status ps_profile_enable(ps_ctx* ctx, int32_t enable);
 PS_API ps_status ps_profile_read(ps_ctx* ctx, int32_t kernel_id, double* total_ms_host, int64_t* launches_host);
 PS_API int32_t ps_profile_kernel_count(void);

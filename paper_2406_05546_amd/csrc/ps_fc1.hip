@@ -66,29 +66,28 @@ struct Fc1DwEpi {
     }
 };
 
-inline dim3 gemm_grid(int M, int N, int n) { return dim3((M + GEMM_BM - 1) / GEMM_BM, (N + GEMM_BN - 1) / GEMM_BN, n); }
-
 }  // namespace
 
+// All three use 128 x 128 block tiles (four wavefronts of 64 x 64), K stepped 16 at a time.
+
+// forward: rows = 512 units (W3, k-contiguous), columns = the worker's samples (pool2, k-contiguous)
 void launch_fc1_fwd(const WorkerBuffers& wb, hipStream_t s)
 {
-    GemmShape sh{FC1, wb.B, P2_SIZE, P2_SIZE, P2_SIZE};
-    hipLaunchKernelGGL((gemm_f32_mfma<true, true, Fc1FwdEpi>), gemm_grid(sh.M, sh.N, wb.n), dim3(256), 0, s, sh,
-                       Fc1FwdEpi{wb});
+    gemm_launch<true, true, 2, 2, 2, 2, 16, 1>(FC1, wb.B, P2_SIZE, P2_SIZE, P2_SIZE, wb.n, Fc1FwdEpi{wb}, s);
 }
 
+// weight gradient: rows = 512 units (d3, row-contiguous), columns = 1568 features (pool2, row-contiguous),
+// contraction over the worker's samples
 void launch_fc1_dw(const WorkerBuffers& wb, hipStream_t s)
 {
-    GemmShape dw{FC1, P2_SIZE, wb.B, FC1, P2_SIZE};
-    hipLaunchKernelGGL((gemm_f32_mfma<false, false, Fc1DwEpi>), gemm_grid(dw.M, dw.N, wb.n), dim3(256), 0, s, dw,
-                       Fc1DwEpi{wb});
+    gemm_launch<false, false, 2, 2, 2, 2, 16, 1>(FC1, P2_SIZE, wb.B, FC1, P2_SIZE, wb.n, Fc1DwEpi{wb}, s);
 }
 
+// input gradient: rows = 1568 features (W3, row-contiguous), columns = samples (d3, k-contiguous),
+// contraction over the 512 units
 void launch_fc1_dx(const WorkerBuffers& wb, hipStream_t s)
 {
-    GemmShape dx{P2_SIZE, wb.B, FC1, P2_SIZE, FC1};
-    hipLaunchKernelGGL((gemm_f32_mfma<false, true, Fc1DxEpi>), gemm_grid(dx.M, dx.N, wb.n), dim3(256), 0, s, dx,
-                       Fc1DxEpi{wb});
+    gemm_launch<false, true, 2, 2, 2, 2, 16, 1>(P2_SIZE, wb.B, FC1, P2_SIZE, FC1, wb.n, Fc1DxEpi{wb}, s);
 }
 
 }  // namespace ps

@@ -2,14 +2,21 @@
 // contractions of the 1568 -> 512 fully connected layer (forward, input gradient, per-worker
 // weight gradient).
 //
-//   C[m][n] = sum_k A(m,k) * B(n,k)        one problem per blockIdx.z (= worker)
+//   C[m][n] = sum_k A(m,k) * B(n,k)        one problem per batch index z (= worker)
 //
 // Either operand may be stored k-contiguous ("KC": element (r,k) at base[r*ld + k]) or
-// row-contiguous ("RC": element (r,k) at base[k*ld + r]).  A 256-thread block (4 wavefronts, 2x2)
-// owns a 128x128 tile of C; each wavefront owns 64x64 as 2x2 MFMA tiles.  K advances 16 at a time
-// through double-buffered LDS.  Within a 16-deep stage the contraction index is consumed in the
-// order that lets a lane fetch four consecutive k of a KC operand with one 16-byte LDS read:
-// MFMA step (j,i), j<2, i<4, pairs lane half h with k = 8j + 4h + i for both operands.
+// row-contiguous ("RC": element (r,k) at base[k*ld + r]).  A 256-thread block (4 wavefronts arranged
+// WM x WN) owns a (WM*TM*32) x (WN*TN*32) tile of C; each wavefront owns TM x TN MFMA tiles of 32x32.
+// K advances KS at a time through double-buffered LDS, with the global loads running two stages
+// ahead and everything inside the loop straight-line code, so that loads, LDS writes and address
+// updates issue in the shadow of the 64-cycle MFMAs.  Within a stage the contraction index is
+// consumed in the order that lets a lane fetch four consecutive k of a KC operand with one 16-byte
+// LDS read: MFMA step (j,i), j < KS/8, i < 4, pairs lane half h with k = 8j + 4h + i for both
+// operands.
+//
+// Blocks are numbered so that the blocks of one batch index run next to each other on one XCD (work
+// groups are handed to the 8 XCDs round-robin, each XCD has its own L2): the operand that belongs to
+// the batch index is then fetched from HBM once and re-used out of that L2.
 //
 // The epilogue functor receives four consecutive rows m..m+3 of one column n:
 //   epi(z, m, n, float4 acc)   with m % 4 == 0.
@@ -19,141 +26,199 @@
 namespace ps {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4v __attribute__((ext_vector_type(4)));  // first-class vector: stays in registers
 
-constexpr int GEMM_BM = 128, GEMM_BN = 128, GEMM_KS = 16;
-constexpr int GEMM_KC_LD = GEMM_KS + 4;  // padded row of a KC tile in LDS: 16-byte reads hit distinct banks
-constexpr int GEMM_TILE_FLOATS = 128 * GEMM_KC_LD;  // >= 16 * 128 (RC tile)
+constexpr int GEMM_XCDS = 8;
 
 struct GemmShape {
     int M, N, K;     // M % 4 == 0; K % 4 == 0 when an operand is KC
     int lda, ldb;
+    int gx, gy, gz;  // tiles along M, along N, batch size
 };
 
-// Global -> registers for one 128 x 16 operand stage (two float4 per thread).
-template <bool KC>
-__device__ __forceinline__ void gemm_load_stage(const float* __restrict__ base, int ld, int row0, int nrows, int k0,
-                                                int K, int tid, float4 (&r)[2])
-{
-    if (KC) {
-        const int kc = (tid & 3) * 4;
+// Operand tiles are read with unconditional loads from addresses that are clamped into the operand,
+// so the loop carries no branches and no 64-bit address arithmetic (uniform base + 32-bit offset):
+//   KC operand [nrows][ld]: a row >= nrows reads the last row instead.  It only reaches rows/columns
+//                           of C that are never stored.  K must be a multiple of KS.
+//   RC operand [K][ld]:     four-row groups >= nrows read the last group instead.  If K is not a
+//                           multiple of KS (RAGGED), a k >= K reads k = K-1 and is then replaced by
+//                           zeros, because it is part of the contraction.
+template <int ROWS, int KS, bool KC, bool RAGGED>
+struct GemmOperand {
+    static constexpr int LD = KC ? KS + 4 : ROWS;           // LDS pitch: padded k-row, or one k-plane of ROWS
+    static constexpr int FLOATS = KC ? ROWS * LD : KS * LD;
+    static constexpr int N4 = ROWS * KS / 4, NV = (N4 + 255) / 256;  // float4 per stage, per thread
+
+    const float* base;
+    uint32_t off[NV];     // float offset of this thread's float4 i in stage 0
+    uint32_t last[NV];    // RC only: the same element at k = K-1
+    uint32_t stage_step;  // float distance between consecutive stages
+
+    __device__ __forceinline__ void init(const float* b, int ld, int row0, int nrows, int K, int tid)
+    {
+        base = b;
+        stage_step = KC ? KS : KS * ld;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int row = row0 + (tid >> 2) + 64 * i;
-            r[i] = (row < nrows && k0 + kc < K)
-                       ? *reinterpret_cast<const float4*>(base + (size_t)row * ld + k0 + kc)
-                       : make_float4(0.f, 0.f, 0.f, 0.f);
-        }
-    } else {
-        const int r4 = (tid & 31) * 4;
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int k = k0 + (tid >> 5) + 8 * i;
-            r[i] = (row0 + r4 < nrows && k < K)
-                       ? *reinterpret_cast<const float4*>(base + (size_t)k * ld + row0 + r4)
-                       : make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int i = 0; i < NV; ++i) {
+            const int f = min(tid + 256 * i, N4 - 1);  // threads without an element repeat the last one
+            if (KC) {
+                off[i] = (uint32_t)min(row0 + f / (KS / 4), nrows - 1) * ld + (f % (KS / 4)) * 4;
+                last[i] = 0;
+            } else {
+                const uint32_t row = min(row0 + (f % (ROWS / 4)) * 4, nrows - 4);
+                off[i] = (uint32_t)(f / (ROWS / 4)) * ld + row;
+                last[i] = (uint32_t)(K - 1) * ld + row;
+            }
         }
     }
-}
 
-template <bool KC>
-__device__ __forceinline__ void gemm_store_stage(float* __restrict__ tile, int tid, const float4 (&r)[2])
-{
-    if (KC) {
+    // Global -> registers for stage kt.
+    __device__ __forceinline__ void load(int kt, floatx4v (&r)[NV]) const
+    {
+        const uint32_t so = (uint32_t)kt * stage_step;
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
-            *reinterpret_cast<float4*>(tile + ((tid >> 2) + 64 * i) * GEMM_KC_LD + (tid & 3) * 4) = r[i];
-    } else {
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-            *reinterpret_cast<float4*>(tile + ((tid >> 5) + 8 * i) * 128 + (tid & 31) * 4) = r[i];
+        for (int i = 0; i < NV; ++i) {
+            if (KC || !RAGGED) {
+                r[i] = *reinterpret_cast<const floatx4v*>(base + so + off[i]);
+            } else {
+                const uint32_t o = off[i] + so;
+                const floatx4v v = *reinterpret_cast<const floatx4v*>(base + min(o, last[i]));
+                r[i] = o > last[i] ? floatx4v{0.f, 0.f, 0.f, 0.f} : v;
+            }
+        }
     }
-}
 
-// The four operand values (i = 0..3) a lane feeds to MFMA steps (j, 0..3) for tile row `row`.
-template <bool KC>
-__device__ __forceinline__ float4 gemm_fetch(const float* __restrict__ tile, int row, int j, int h)
-{
-    if (KC) return *reinterpret_cast<const float4*>(tile + row * GEMM_KC_LD + 8 * j + 4 * h);
-    const float* p = tile + (8 * j + 4 * h) * 128 + row;
-    return make_float4(p[0], p[128], p[256], p[384]);
-}
+    static __device__ __forceinline__ void store(float* __restrict__ tile, int tid, const floatx4v (&r)[NV])
+    {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const int f = tid + 256 * i;
+            const int at = KC ? (f / (KS / 4)) * LD + (f % (KS / 4)) * 4 : (f / (ROWS / 4)) * LD + (f % (ROWS / 4)) * 4;
+            if (256 * (i + 1) <= N4 || f < N4) *reinterpret_cast<floatx4v*>(tile + at) = r[i];
+        }
+    }
 
-template <bool A_KC, bool B_KC, class Epi>
-__global__ __launch_bounds__(256) void gemm_f32_mfma(GemmShape sh, Epi epi)
+    // The four operand values (i = 0..3) a lane feeds to MFMA steps (j, 0..3) for tile row `row`.
+    static __device__ __forceinline__ floatx4v fetch(const float* __restrict__ tile, int row, int j, int h)
+    {
+        if (KC) return *reinterpret_cast<const floatx4v*>(tile + row * LD + 8 * j + 4 * h);
+        const float* p = tile + (8 * j + 4 * h) * LD + row;
+        return floatx4v{p[0], p[LD], p[2 * LD], p[3 * LD]};
+    }
+};
+
+template <bool A_KC, bool B_KC, int TM, int TN, int WM, int WN, int KS, bool RAGGED, int MINW, class Epi>
+__global__ __launch_bounds__(256, MINW) void gemm_f32_mfma(GemmShape sh, Epi epi)
 {
-    __shared__ __attribute__((aligned(16))) float lds[2][2][GEMM_TILE_FLOATS];  // [buffer][A|B]
+    static_assert(WM * WN == 4, "four wavefronts per block");
+    constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
+    using OpA = GemmOperand<BM, KS, A_KC, RAGGED>;
+    using OpB = GemmOperand<BN, KS, B_KC, RAGGED>;
+    __shared__ __attribute__((aligned(16))) float lds[2][OpA::FLOATS + OpB::FLOATS];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int h = lane >> 5, l32 = lane & 31;
-    const int wm = wave & 1, wn = wave >> 1;
-    const int z = blockIdx.z;
-    const int m0 = blockIdx.x * GEMM_BM, n0 = blockIdx.y * GEMM_BN;
+    const int wm = wave % WM, wn = wave / WM;
+
+    // XCD-aware numbering: XCD x (= linear id mod 8) walks a contiguous range of (z, y, x) triples.
+    const int total = sh.gx * sh.gy * sh.gz, per_xcd = (total + GEMM_XCDS - 1) / GEMM_XCDS;
+    const int v = (blockIdx.x % GEMM_XCDS) * per_xcd + blockIdx.x / GEMM_XCDS;
+    if (v >= total) return;
+    const int m0 = (v % sh.gx) * BM, n0 = (v / sh.gx % sh.gy) * BN, z = v / (sh.gx * sh.gy);
     const float* __restrict__ A = epi.a_ptr(z);
     const float* __restrict__ B = epi.b_ptr(z);
 
-    floatx16 acc[2][2];
+    floatx16 acc[TM][TN];
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < TM; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < TN; ++b)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
-    float4 ra[2], rb[2];
-    gemm_load_stage<A_KC>(A, sh.lda, m0, sh.M, 0, sh.K, tid, ra);
-    gemm_load_stage<B_KC>(B, sh.ldb, n0, sh.N, 0, sh.K, tid, rb);
-    gemm_store_stage<A_KC>(lds[0][0], tid, ra);
-    gemm_store_stage<B_KC>(lds[0][1], tid, rb);
+    // Three-deep pipeline: while the matrix cores consume stage kt out of one LDS buffer, stage kt+1
+    // (loaded from HBM/L2 during the previous iteration) is written into the other buffer half way
+    // through, and the loads of stage kt+2 are issued right behind that write.
+    floatx4v ra[OpA::NV], rb[OpB::NV];
+    const int nk = (sh.K + KS - 1) / KS;
+    OpA opa;
+    OpB opb;
+    opa.init(A, sh.lda, m0, sh.M, sh.K, tid);
+    opb.init(B, sh.ldb, n0, sh.N, sh.K, tid);
+    {
+        floatx4v ra0[OpA::NV], rb0[OpB::NV];  // stages 0 and 1 are in flight together
+        opa.load(0, ra0);
+        opb.load(0, rb0);
+        opa.load(min(1, nk - 1), ra);
+        opb.load(min(1, nk - 1), rb);
+        OpA::store(lds[0], tid, ra0);
+        OpB::store(lds[0] + OpA::FLOATS, tid, rb0);
+    }
     __syncthreads();
 
-    const int nk = (sh.K + GEMM_KS - 1) / GEMM_KS;
     for (int kt = 0; kt < nk; ++kt) {
         const int cur = kt & 1;
-        if (kt + 1 < nk) {
-            gemm_load_stage<A_KC>(A, sh.lda, m0, sh.M, (kt + 1) * GEMM_KS, sh.K, tid, ra);
-            gemm_load_stage<B_KC>(B, sh.ldb, n0, sh.N, (kt + 1) * GEMM_KS, sh.K, tid, rb);
-        }
-        const float* ta = lds[cur][0];
-        const float* tb = lds[cur][1];
+        const float* ta = lds[cur];
+        const float* tb = lds[cur] + OpA::FLOATS;
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            float4 fa[2], fb[2];
+        for (int j = 0; j < KS / 8; ++j) {
+            floatx4v fa[TM], fb[TN];
 #pragma unroll
-            for (int a = 0; a < 2; ++a) fa[a] = gemm_fetch<A_KC>(ta, wm * 64 + a * 32 + l32, j, h);
+            for (int a = 0; a < TM; ++a) fa[a] = OpA::fetch(ta, (wm * TM + a) * 32 + l32, j, h);
 #pragma unroll
-            for (int b = 0; b < 2; ++b) fb[b] = gemm_fetch<B_KC>(tb, wn * 64 + b * 32 + l32, j, h);
+            for (int b = 0; b < TN; ++b) fb[b] = OpB::fetch(tb, (wn * TN + b) * 32 + l32, j, h);
 #pragma unroll
-            for (int a = 0; a < 2; ++a)
+            for (int a = 0; a < TM; ++a)
 #pragma unroll
-                for (int b = 0; b < 2; ++b) {
+                for (int b = 0; b < TN; ++b) {
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[a].x, fb[b].x, acc[a][b], 0, 0, 0);
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[a].y, fb[b].y, acc[a][b], 0, 0, 0);
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[a].z, fb[b].z, acc[a][b], 0, 0, 0);
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[a].w, fb[b].w, acc[a][b], 0, 0, 0);
                 }
-        }
-        if (kt + 1 < nk) {
-            gemm_store_stage<A_KC>(lds[cur ^ 1][0], tid, ra);
-            gemm_store_stage<B_KC>(lds[cur ^ 1][1], tid, rb);
+            if (j == KS / 16 - 1) {
+                // unconditional on purpose (straight-line code schedules under the MFMAs): past the
+                // end the last stage is simply loaded and stored again where nobody reads it
+                OpA::store(lds[cur ^ 1], tid, ra);
+                OpB::store(lds[cur ^ 1] + OpA::FLOATS, tid, rb);
+                opa.load(min(kt + 2, nk - 1), ra);
+                opb.load(min(kt + 2, nk - 1), rb);
+            }
         }
         __syncthreads();
     }
 
-    // Accumulator register v of lane (h, l32) holds C[8*(v/4) + 4*h + v%4][l32] of its 32x32 tile.
+    // Accumulator register i of lane (h, l32) holds C[8*(i/4) + 4*h + i%4][l32] of its 32x32 tile.
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < TM; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b) {
-            const int n = n0 + wn * 64 + b * 32 + l32;
+        for (int b = 0; b < TN; ++b) {
+            const int n = n0 + (wn * TN + b) * 32 + l32;
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const int m = m0 + wm * 64 + a * 32 + 8 * g + 4 * h;
+                const int m = m0 + (wm * TM + a) * 32 + 8 * g + 4 * h;
                 if (m < sh.M && n < sh.N)
                     epi(z, m, n,
                         make_float4(acc[a][b][4 * g], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2], acc[a][b][4 * g + 3]));
             }
         }
+}
+
+// Launches one GEMM per batch index over a 1-D grid padded to a multiple of the XCD count.
+template <bool A_KC, bool B_KC, int TM, int TN, int WM, int WN, int KS, int MINW, class Epi>
+void gemm_launch(int M, int N, int K, int lda, int ldb, int batch, const Epi& epi, hipStream_t s)
+{
+    constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
+    GemmShape sh{M, N, K, lda, ldb, (M + BM - 1) / BM, (N + BN - 1) / BN, batch};
+    const int total = sh.gx * sh.gy * sh.gz;
+    const int grid = (total + GEMM_XCDS - 1) / GEMM_XCDS * GEMM_XCDS;
+    if (K % KS == 0)
+        hipLaunchKernelGGL((gemm_f32_mfma<A_KC, B_KC, TM, TN, WM, WN, KS, false, MINW, Epi>), dim3(grid), dim3(256), 0, s,
+                           sh, epi);
+    else
+        hipLaunchKernelGGL((gemm_f32_mfma<A_KC, B_KC, TM, TN, WM, WN, KS, true, MINW, Epi>), dim3(grid), dim3(256), 0, s,
+                           sh, epi);
 }
 
 }  // namespace ps

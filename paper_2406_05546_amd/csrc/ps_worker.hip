@@ -94,8 +94,8 @@ hipError_t launch_worker_backward(const WorkerBuffers& wb, hipStream_t s, Profil
 const char* kernel_name(int id)
 {
     static const char* const names[K_COUNT] = {
-        "conv1_fwd_kernel", "conv2_fwd_kernel", "gemm_f32_mfma<true, true, Fc1FwdEpi>", "fc2_kernel",
-        "gemm_f32_mfma<false, false, Fc1DwEpi>", "gemm_f32_mfma<false, true, Fc1DxEpi>", "conv2_dw_kernel",
+        "conv1_fwd_kernel", "conv2_fwd_kernel", "gemm_f32_mfma<Fc1FwdEpi>", "fc2_kernel",
+        "gemm_f32_mfma<Fc1DwEpi>", "gemm_f32_mfma<Fc1DxEpi>", "conv2_dw_kernel",
         "conv2_dx_kernel", "grad_reduce_kernel", "apply_kernel<0>", "apply_kernel<1>"};
     return id >= 0 && id < K_COUNT ? names[id] : "";
 }
