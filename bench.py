@@ -38,6 +38,19 @@ KERNEL_FLOP_PER_IMAGE = {
     "grad_reduce_kernel": 0,
 }
 APPLY_KERNELS = ("apply_kernel<0>", "apply_kernel<1>")
+# HBM bytes per launch of this workload from the rocprofv3 FETCH_SIZE / WRITE_SIZE passes summarised in
+# profiles/bench_outage_w256_b256_hbm_counters.txt (each scaled by what the same counter reads for the
+# plain 1 GiB copy: x2.000 and x1.000), taken with the kernels as they are in this tree.  A kernel
+# that changes afterwards must be set to None here until its counters are taken again.
+MIB = 1 << 20
+MEASURED_HBM_BYTES = {
+    "conv1_fwd_kernel": (200.2 + 980.0) * MIB, "conv2_fwd_kernel": (785.2 + 494.5) * MIB,
+    "gemm_f32_mfma<Fc1FwdEpi>": (578.7 + 130.6) * MIB, "fc2_kernel": (129.0 + 175.1) * MIB,
+    "gemm_f32_mfma<Fc1DwEpi>": (528.4 + 784.0) * MIB, "gemm_f32_mfma<Fc1DxEpi>": (1171.9 + 409.7) * MIB,
+    "conv2_dw_kernel": (1274.2 + 145.0) * MIB, "conv2_dx_kernel": (883.0 + 5.0) * MIB,
+    "grad_reduce_kernel": (194.8 + 10.2) * MIB, "apply_kernel<0>": (3180.1 + 3.1) * MIB,
+    "apply_kernel<1>": (3180.1 + 3.1) * MIB,
+}
 
 
 def cpu_baseline():
@@ -145,7 +158,8 @@ def main():
     kernels.sort(key=lambda k: -k["total_ms"])
     dom = kernels[0]
     roofline = {k: dom[k] for k in ("bound", "achieved", "peak", "unit", "frac")}
-    roofline.update({"kernel": dom["kernel"], "avg_ms": dom["avg_ms"], "traffic": None})
+    roofline.update({"kernel": dom["kernel"], "avg_ms": dom["avg_ms"], "traffic": MEASURED_HBM_BYTES.get(dom["kernel"]),
+                     "traffic_unit": "bytes per launch (HBM, measured)"})
     drains = [k for k in kernels if k["kernel"] in APPLY_KERNELS]
     worker_ms = sum(k["total_ms"] for k in kernels if k["kernel"] not in APPLY_KERNELS)
     worker_tflops = FLOP_PER_IMAGE * images_per_step * args.steps / (worker_ms * 1e-3) / 1e12 if worker_ms else 0.0
@@ -162,7 +176,8 @@ def main():
         "worker_kernels_sum": {"achieved": worker_tflops, "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s",
                                "frac": worker_tflops / PEAK_MFMA_F32_TFLOPS,
                                "images_per_s_kernel_time": images_per_step * args.steps / (worker_ms * 1e-3)},
-        "drain": [{k: d[k] for k in ("kernel", "avg_ms", "achieved", "peak", "unit", "frac", "launches")}
+        "drain": [dict({k: d[k] for k in ("kernel", "avg_ms", "achieved", "peak", "unit", "frac", "launches")},
+                       algorithmic_bytes=W * ROUNDS * P * 4 + 2 * P * 4, traffic=MEASURED_HBM_BYTES.get(d["kernel"]))
                   for d in drains],
         "kernels": [{k: v for k, v in kk.items() if k != "total_ms"} for kk in kernels],
         "final_mean_loss": final_loss,

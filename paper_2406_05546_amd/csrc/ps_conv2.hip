@@ -104,7 +104,7 @@ struct D2Stage {
 // accumulators of a lane are one 2x2 pool window; columns are the 32 output channels (two 16-wide
 // MFMA tiles sharing the A operand); K = (tap, channel).  A block owns up to FWD_IPB images of one
 // worker and walks them FWD_G at a time (196 pooled positions = 49 row tiles per group).
-constexpr int FWD_G = 4, FWD_IPB = 16;
+constexpr int FWD_G = 4, FWD_IPB = 32;
 
 __global__ __launch_bounds__(256, 2) void conv2_fwd_kernel(WorkerBuffers wb, int blocks_per_worker)
 {
@@ -175,7 +175,7 @@ __global__ __launch_bounds__(256, 2) void conv2_fwd_kernel(WorkerBuffers wb, int
 //   d W1[c][dy][dx] += d pool1[c][p] * xpad[winner(c,p) + (dy,dx)],   d b1[c] += d pool1[c][p],
 // on the vector ALU, which is idle while the matrix cores run.  A block owns up to DX_IPB images of
 // one worker and walks them DX_G at a time; each wavefront's conv1 sums go to its own partial slot.
-constexpr int DX_G = 2, DX_IPB = 16;
+constexpr int DX_G = 2, DX_IPB = 32;
 
 __global__ __launch_bounds__(256, 2) void conv2_dx_kernel(WorkerBuffers wb, int blocks_per_worker)
 {
