@@ -141,6 +141,21 @@ PS_API ps_status ps_apply_async(ps_ctx* ctx, int32_t queue_index, float lr);
  * queue.  *n_applied_host (may be NULL) receives K; K = 0 changes nothing. */
 PS_API ps_status ps_drain_buffered(ps_ctx* ctx, int32_t mode, float lr, int32_t* n_applied_host);
 
+/* Recovery with the mitigations the paper reports or suggests for large backlogs of stale gradients
+ * (Section 2.3, last paragraph): the learning rate is turned down with the number K of pending
+ * gradients, lr_used = lr * min(1, lr_backlog_ref / K) (lr_backlog_ref = 0 switches this off), and
+ * every gradient is clipped to 2-norm clip_norm, g := g * min(1, clip_norm / ||g||_2) (clip_norm = 0
+ * switches this off; the norm costs one extra pass over the queue).  Otherwise as ps_drain_buffered.
+ * *lr_used_host (may be NULL) receives the learning rate applied.  The paper gives no formula for
+ * either; these are this library's readings. */
+typedef struct {
+    float lr;
+    float lr_backlog_ref; /* >= 0 */
+    float clip_norm;      /* >= 0 */
+} ps_drain_policy;
+PS_API ps_status ps_drain_buffered_mitigated(ps_ctx* ctx, int32_t mode, const ps_drain_policy* policy,
+                                      int32_t* n_applied_host, float* lr_used_host);
+
 /* Copies pending gradient `queue_index` (P floats) to the host. */
 PS_API ps_status ps_get_grad(ps_ctx* ctx, int32_t queue_index, float* grad_host);
 

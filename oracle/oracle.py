@@ -217,6 +217,33 @@ def drain(theta: np.ndarray, pending: Sequence[np.ndarray], lr: float, mode: int
     return theta
 
 
+def clip_scales(pending: Sequence[np.ndarray], clip_norm: float) -> List[float]:
+    """Per-gradient factor min(1, clip_norm / ||g||_2); 1 where clipping is off or the gradient is zero."""
+    out = []
+    for g in pending:
+        norm = float(np.sqrt(np.sum(np.asarray(g, dtype=np.float64) ** 2)))
+        out.append(clip_norm / norm if (clip_norm > 0 and norm > clip_norm) else 1.0)
+    return out
+
+
+def backlog_lr(lr: float, n_pending: int, lr_backlog_ref: float) -> float:
+    """Learning rate turned down for a large backlog: lr * min(1, ref / K); ref = 0 leaves lr alone."""
+    if lr_backlog_ref > 0 and n_pending > lr_backlog_ref:
+        return lr * (lr_backlog_ref / n_pending)
+    return lr
+
+
+def drain_mitigated(theta: np.ndarray, pending: Sequence[np.ndarray], lr: float, mode: int, lr_backlog_ref: float,
+                    clip_norm: float):
+    """Recovery drain with the stale-gradient mitigations of Section 2.3's last paragraph (the paper names
+    them without formulas; these are this build's readings): each pending gradient is clipped to
+    2-norm clip_norm and the learning rate is scaled by min(1, lr_backlog_ref / K).
+    Returns (new theta, learning rate used)."""
+    used = backlog_lr(lr, len(pending), lr_backlog_ref)
+    scaled = [np.asarray(g, dtype=np.float64) * s for g, s in zip(pending, clip_scales(pending, clip_norm))]
+    return drain(theta, scaled, used, mode), used
+
+
 # --------------------------------------------------------------------------- server model
 
 @dataclass
@@ -291,9 +318,9 @@ class OracleServer:
         self.theta = apply_async(self.theta, e.grad, lr)
         self.version += 1
 
-    def drain_buffered(self, mode: int, lr: float) -> int:
+    def drain_buffered(self, mode: int, lr: float, lr_backlog_ref: float = 0.0, clip_norm: float = 0.0) -> int:
         k = len(self.pending)
-        self.theta = drain(self.theta, [e.grad for e in self.pending], lr, mode)
+        self.theta, _ = drain_mitigated(self.theta, [e.grad for e in self.pending], lr, mode, lr_backlog_ref, clip_norm)
         self.version += 0 if k == 0 else (1 if mode == DRAIN_SUM else k)
         self.pending = []
         return k

@@ -41,7 +41,7 @@ class OracleReplay:
             elif kind == "async":
                 sv.apply_async(ev[1], ev[2])
             elif kind == "drain":
-                sv.drain_buffered(ev[1], ev[2])
+                sv.drain_buffered(*ev[1:])
             elif kind == "snapshot":
                 sv.snapshot_weights(ev[1])
             else:

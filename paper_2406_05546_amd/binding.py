@@ -27,7 +27,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libps_hotpa
 
 EXPORTS = ["ps_workspace_bytes", "ps_init", "ps_destroy", "ps_sync", "ps_set_weights", "ps_get_weights",
            "ps_snapshot_weights", "worker_grads_batched", "ps_queue_push_host", "ps_apply_sync", "ps_apply_async",
-           "ps_drain_buffered", "ps_get_grad", "ps_queue_meta", "ps_version", "ps_debug_last_batch", "ps_profile_enable", "ps_profile_read", "ps_profile_kernel_count",
+           "ps_drain_buffered", "ps_drain_buffered_mitigated", "ps_get_grad", "ps_queue_meta", "ps_version", "ps_debug_last_batch", "ps_profile_enable", "ps_profile_read", "ps_profile_kernel_count",
            "ps_profile_kernel_name", "ps_last_error"]
 
 
@@ -35,6 +35,10 @@ class PsError(RuntimeError):
     def __init__(self, call: str, status: int, message: str = ""):
         super().__init__(f"{call}: {_STATUS.get(status, status)} {message}".strip())
         self.status = status
+
+
+class ps_drain_policy(ctypes.Structure):
+    _fields_ = [("lr", ctypes.c_float), ("lr_backlog_ref", ctypes.c_float), ("clip_norm", ctypes.c_float)]
 
 
 class ps_config(ctypes.Structure):
@@ -63,6 +67,8 @@ def load_library() -> ctypes.CDLL:
             "ps_queue_push_host": [vp, vp, i32, u64, u64, ctypes.POINTER(i32)],
             "ps_apply_sync": [vp, vp, i32, f32], "ps_apply_async": [vp, i32, f32],
             "ps_drain_buffered": [vp, i32, f32, ctypes.POINTER(i32)],
+            "ps_drain_buffered_mitigated": [vp, i32, ctypes.POINTER(ps_drain_policy), ctypes.POINTER(i32),
+                                            ctypes.POINTER(f32)],
             "ps_get_grad": [vp, i32, vp],
             "ps_queue_meta": [vp, i32, ctypes.POINTER(i32), vp, vp, vp, vp, vp],
             "ps_version": [vp, ctypes.POINTER(u64)],
@@ -212,6 +218,16 @@ def ps_drain_buffered(ctx: Context, mode: int, lr: float) -> int:
     k = ctypes.c_int32(0)
     _check(ctx, "ps_drain_buffered", load_library().ps_drain_buffered(ctx.handle, mode, lr, ctypes.byref(k)))
     return int(k.value)
+
+
+def ps_drain_buffered_mitigated(ctx: Context, mode: int, lr: float, lr_backlog_ref: float = 0.0,
+                                clip_norm: float = 0.0) -> Tuple[int, float]:
+    """Returns (number of gradients applied, learning rate used)."""
+    pol = ps_drain_policy(lr, lr_backlog_ref, clip_norm)
+    k, used = ctypes.c_int32(0), ctypes.c_float(0.0)
+    st = load_library().ps_drain_buffered_mitigated(ctx.handle, mode, ctypes.byref(pol), ctypes.byref(k), ctypes.byref(used))
+    _check(ctx, "ps_drain_buffered_mitigated", st)
+    return int(k.value), float(used.value)
 
 
 def ps_get_grad(ctx: Context, queue_index: int) -> np.ndarray:

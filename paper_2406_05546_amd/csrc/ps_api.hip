@@ -45,7 +45,7 @@ struct Carve {
 };
 
 struct Layout {
-    uint64_t theta, ring, queue, meta, idx, p1, am1, p2, am2, ht, z, pred, d3, dp2g, part, part1, fpart, keep, total;
+    uint64_t theta, ring, queue, meta, idx, p1, am1, p2, am2, ht, z, pred, d3, dp2g, part, part1, fpart, normpart, scale, keep, total;
 };
 
 bool config_ok(const ps_config* c)
@@ -76,6 +76,8 @@ Layout make_layout(const ps_config& c)
     l.part = k.take((uint64_t)c.max_workers * N_PART * CONV_PART * 4);
     l.part1 = k.take((uint64_t)c.max_workers * conv1_part_slots(c.batch) * OFF_W2 * 4);
     l.fpart = k.take((uint64_t)4 * (512 + c.max_workers) * FC2_PART * 4);  // >= n * 4 * fc2_split(n) slots
+    l.normpart = k.take((uint64_t)c.queue_capacity * norm_slices() * 4);
+    l.scale = k.take((uint64_t)c.queue_capacity * 4);
     l.keep = k.take((uint64_t)c.batch * FC1);
     l.total = k.off;
     return l;
@@ -386,6 +388,33 @@ ps_status ps_drain_buffered(ps_ctx* c, int32_t mode, float lr, int32_t* n_applie
     if (idx.empty()) return PS_OK;
     ps_status st = apply_entries(c, idx, lr, mode);
     if (st != PS_OK) return st;
+    release_entries(c, idx);
+    c->version += mode == PS_DRAIN_SUM ? 1 : idx.size();
+    return PS_OK;
+}
+
+ps_status ps_drain_buffered_mitigated(ps_ctx* c, int32_t mode, const ps_drain_policy* pol, int32_t* n_applied_host,
+                                      float* lr_used_host)
+{
+    if (!c) return PS_EINVAL;
+    if (!pol || (mode != PS_DRAIN_SUM && mode != PS_DRAIN_SEQ) || !(pol->lr_backlog_ref >= 0.f) || !(pol->clip_norm >= 0.f))
+        return fail(c, PS_EINVAL, "ps_drain_buffered_mitigated: bad mode or policy");
+    const std::vector<int32_t> idx = c->pending;
+    const float K = (float)idx.size();
+    const float lr = (pol->lr_backlog_ref > 0.f && K > pol->lr_backlog_ref) ? pol->lr * (pol->lr_backlog_ref / K) : pol->lr;
+    if (n_applied_host) *n_applied_host = (int32_t)idx.size();
+    if (lr_used_host) *lr_used_host = lr;
+    if (idx.empty()) return PS_OK;
+    if (pol->clip_norm > 0.f) {
+        ps_status st = upload(c, c->at<int32_t>(c->lay.idx), idx.data(), idx.size() * sizeof(int32_t));
+        if (st != PS_OK) return st;
+        PS_HIP(c, launch_apply_clipped(c->theta(), c->at<float>(c->lay.queue), c->at<int32_t>(c->lay.idx), (int)idx.size(),
+                                       lr, mode, pol->clip_norm, c->at<float>(c->lay.normpart), c->at<float>(c->lay.scale),
+                                       c->stream, c->prof));
+    } else {
+        ps_status st = apply_entries(c, idx, lr, mode);
+        if (st != PS_OK) return st;
+    }
     release_entries(c, idx);
     c->version += mode == PS_DRAIN_SUM ? 1 : idx.size();
     return PS_OK;

@@ -19,9 +19,11 @@ __device__ __forceinline__ float4 ld_stream(const float4* p)
     return make_float4(v.x, v.y, v.z, v.w);
 }
 
-template <int MODE>
+// SCALED: gradient k is multiplied by scale[k] first (norm clipping of stale gradients).
+template <int MODE, bool SCALED>
 __global__ __launch_bounds__(256) void apply_kernel(float4* __restrict__ theta, const float4* __restrict__ queue,
-                                                     const int32_t* __restrict__ idx, int K, float lr)
+                                                     const int32_t* __restrict__ idx, int K, float lr,
+                                                     const float* __restrict__ scale)
 {
     const int i = blockIdx.x * 256 + threadIdx.x;
     if (i >= ROW4) return;
@@ -35,21 +37,31 @@ __global__ __launch_bounds__(256) void apply_kernel(float4* __restrict__ theta, 
         for (int u = 0; u < UNROLL; ++u) g[u] = ld_stream(col + (size_t)idx[k + u] * ROW4);
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
+            const float c = SCALED ? scale[k + u] : 1.f;
             if (MODE == 0) {
-                s.x += g[u].x; s.y += g[u].y; s.z += g[u].z; s.w += g[u].w;
+                if (SCALED) {
+                    s.x = fmaf(c, g[u].x, s.x); s.y = fmaf(c, g[u].y, s.y);
+                    s.z = fmaf(c, g[u].z, s.z); s.w = fmaf(c, g[u].w, s.w);
+                } else {
+                    s.x += g[u].x; s.y += g[u].y; s.z += g[u].z; s.w += g[u].w;
+                }
             } else {
-                t.x = fmaf(-lr, g[u].x, t.x); t.y = fmaf(-lr, g[u].y, t.y);
-                t.z = fmaf(-lr, g[u].z, t.z); t.w = fmaf(-lr, g[u].w, t.w);
+                const float a = SCALED ? -lr * c : -lr;
+                t.x = fmaf(a, g[u].x, t.x); t.y = fmaf(a, g[u].y, t.y);
+                t.z = fmaf(a, g[u].z, t.z); t.w = fmaf(a, g[u].w, t.w);
             }
         }
     }
     for (; k < K; ++k) {
         float4 g = ld_stream(col + (size_t)idx[k] * ROW4);
+        const float c = SCALED ? scale[k] : 1.f;
         if (MODE == 0) {
-            s.x += g.x; s.y += g.y; s.z += g.z; s.w += g.w;
+            s.x = fmaf(c, g.x, s.x); s.y = fmaf(c, g.y, s.y);
+            s.z = fmaf(c, g.z, s.z); s.w = fmaf(c, g.w, s.w);
         } else {
-            t.x = fmaf(-lr, g.x, t.x); t.y = fmaf(-lr, g.y, t.y);
-            t.z = fmaf(-lr, g.z, t.z); t.w = fmaf(-lr, g.w, t.w);
+            const float a = -lr * c;
+            t.x = fmaf(a, g.x, t.x); t.y = fmaf(a, g.y, t.y);
+            t.z = fmaf(a, g.z, t.z); t.w = fmaf(a, g.w, t.w);
         }
     }
     if (MODE == 0) {
@@ -57,6 +69,42 @@ __global__ __launch_bounds__(256) void apply_kernel(float4* __restrict__ theta, 
         t.z = fmaf(-lr, s.z, t.z); t.w = fmaf(-lr, s.w, t.w);
     }
     theta[i] = t;
+}
+
+// Squared 2-norm of queue rows, first pass: block (b, k) sums the squares of slice b of row idx[k]
+// (the row padding is zero) and writes one partial; fixed slices and a fixed tree keep it reproducible.
+constexpr int NORM_SLICES = 32;
+
+__global__ __launch_bounds__(256) void grad_sqnorm_kernel(const float4* __restrict__ queue, const int32_t* __restrict__ idx,
+                                                          float* __restrict__ partial)
+{
+    __shared__ float red[4];
+    const int k = blockIdx.y, b = blockIdx.x;
+    constexpr int PER = (ROW4 + NORM_SLICES - 1) / NORM_SLICES;
+    const float4* row = queue + (size_t)idx[k] * ROW4;
+    const int end = min(ROW4, (b + 1) * PER);
+    float acc = 0.f;
+    for (int i = b * PER + threadIdx.x; i < end; i += 256) {
+        const float4 g = ld_stream(row + i);
+        acc = fmaf(g.x, g.x, acc); acc = fmaf(g.y, g.y, acc); acc = fmaf(g.z, g.z, acc); acc = fmaf(g.w, g.w, acc);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) partial[k * NORM_SLICES + b] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+// Second pass: scale[k] = min(1, clip / ||g_k||_2)  (1 for a zero gradient).
+__global__ __launch_bounds__(256) void clip_scale_kernel(const float* __restrict__ partial, float* __restrict__ scale, int K,
+                                                         float clip)
+{
+    const int k = blockIdx.x * 256 + threadIdx.x;
+    if (k >= K) return;
+    float sq = 0.f;
+    for (int b = 0; b < NORM_SLICES; ++b) sq += partial[k * NORM_SLICES + b];
+    const float norm = sqrtf(sq);
+    scale[k] = norm > clip ? clip / norm : 1.f;
 }
 
 }  // namespace
@@ -68,11 +116,35 @@ hipError_t launch_apply(float* theta, const float* queue, const int32_t* idx_dev
     dim3 grid((ROW4 + 255) / 256), block(256);
     prof.begin(mode == 0 ? K_APPLY_SUM : K_APPLY_SEQ, s);
     if (mode == 0)
-        hipLaunchKernelGGL(apply_kernel<0>, grid, block, 0, s, (float4*)theta, (const float4*)queue, idx_dev, K, lr);
+        hipLaunchKernelGGL((apply_kernel<0, false>), grid, block, 0, s, (float4*)theta, (const float4*)queue, idx_dev, K, lr,
+                           (const float*)nullptr);
     else
-        hipLaunchKernelGGL(apply_kernel<1>, grid, block, 0, s, (float4*)theta, (const float4*)queue, idx_dev, K, lr);
+        hipLaunchKernelGGL((apply_kernel<1, false>), grid, block, 0, s, (float4*)theta, (const float4*)queue, idx_dev, K, lr,
+                           (const float*)nullptr);
     prof.end(s);
     return hipGetLastError();
 }
+
+hipError_t launch_apply_clipped(float* theta, const float* queue, const int32_t* idx_dev, int K, float lr, int mode,
+                                float clip, float* partial_dev, float* scale_dev, hipStream_t s, Profiler& prof)
+{
+    if (K <= 0) return hipSuccess;
+    prof.begin(K_GRAD_SQNORM, s);
+    hipLaunchKernelGGL(grad_sqnorm_kernel, dim3(NORM_SLICES, K), dim3(256), 0, s, (const float4*)queue, idx_dev, partial_dev);
+    prof.end(s);
+    hipLaunchKernelGGL(clip_scale_kernel, dim3((K + 255) / 256), dim3(256), 0, s, partial_dev, scale_dev, K, clip);
+    dim3 grid((ROW4 + 255) / 256), block(256);
+    prof.begin(mode == 0 ? K_APPLY_SUM_CLIP : K_APPLY_SEQ_CLIP, s);
+    if (mode == 0)
+        hipLaunchKernelGGL((apply_kernel<0, true>), grid, block, 0, s, (float4*)theta, (const float4*)queue, idx_dev, K, lr,
+                           (const float*)scale_dev);
+    else
+        hipLaunchKernelGGL((apply_kernel<1, true>), grid, block, 0, s, (float4*)theta, (const float4*)queue, idx_dev, K, lr,
+                           (const float*)scale_dev);
+    prof.end(s);
+    return hipGetLastError();
+}
+
+int norm_slices() { return NORM_SLICES; }
 
 }  // namespace ps

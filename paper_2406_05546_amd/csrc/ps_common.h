@@ -97,7 +97,7 @@ void launch_conv2_dw(const WorkerBuffers& wb, hipStream_t s);
 // Kernels of the path, in launch order; ids index the per-kernel timing table.
 enum KernelId {
     K_CONV1_FWD, K_CONV2_FWD, K_FC1_FWD, K_FC2, K_FC1_DW, K_FC1_DX, K_CONV2_DW, K_CONV2_DX,
-    K_GRAD_REDUCE, K_APPLY_SUM, K_APPLY_SEQ, K_COUNT
+    K_GRAD_REDUCE, K_APPLY_SUM, K_APPLY_SEQ, K_GRAD_SQNORM, K_APPLY_SUM_CLIP, K_APPLY_SEQ_CLIP, K_COUNT
 };
 const char* kernel_name(int id);
 
@@ -129,5 +129,10 @@ hipError_t launch_keep_mask(uint8_t* keep_dev, int B, uint32_t mb_lo, uint32_t m
 // theta -= lr * (sum of the K listed queue rows) [mode 0] or K successive updates [mode 1].
 hipError_t launch_apply(float* theta, const float* queue, const int32_t* idx_dev, int K, float lr, int mode,
                         hipStream_t s, Profiler& prof);
+
+// Same with every gradient first scaled by min(1, clip / ||g||_2): a norm pass, then the apply pass.
+hipError_t launch_apply_clipped(float* theta, const float* queue, const int32_t* idx_dev, int K, float lr, int mode,
+                                float clip, float* partial_dev, float* scale_dev, hipStream_t s, Profiler& prof);
+int norm_slices();
 
 }  // namespace ps

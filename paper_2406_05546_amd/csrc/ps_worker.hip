@@ -96,7 +96,8 @@ const char* kernel_name(int id)
     static const char* const names[K_COUNT] = {
         "conv1_fwd_kernel", "conv2_fwd_kernel", "gemm_f32_mfma<Fc1FwdEpi>", "fc2_kernel",
         "gemm_f32_mfma<Fc1DwEpi>", "gemm_f32_mfma<Fc1DxEpi>", "conv2_dw_kernel",
-        "conv2_dx_kernel", "grad_reduce_kernel", "apply_kernel<0>", "apply_kernel<1>"};
+        "conv2_dx_kernel", "grad_reduce_kernel", "apply_kernel<0>", "apply_kernel<1>", "grad_sqnorm_kernel",
+        "apply_kernel<0, clip>", "apply_kernel<1, clip>"};
     return id >= 0 && id < K_COUNT ? names[id] : "";
 }
 

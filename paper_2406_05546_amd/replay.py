@@ -57,7 +57,10 @@ class Replay:
             elif kind == "async":
                 ps.ps_apply_async(self.ctx, self.entry_of.pop(ev[1]), ev[2])
             elif kind == "drain":
-                k = ps.ps_drain_buffered(self.ctx, ev[1], ev[2])
+                if len(ev) > 3 and (ev[3] or ev[4]):
+                    k, _ = ps.ps_drain_buffered_mitigated(self.ctx, ev[1], ev[2], ev[3], ev[4])
+                else:
+                    k = ps.ps_drain_buffered(self.ctx, ev[1], ev[2])
                 assert k == len(self.entry_of)
                 self.entry_of.clear()
             elif kind == "snapshot":

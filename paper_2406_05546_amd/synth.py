@@ -178,7 +178,9 @@ class OutagePlan:
 #                                       snapshot; gradients get consecutive arrival numbers (seq)
 #   ("sync", seqs, lr)                  one update with all listed gradients
 #   ("async", seq, lr)                  one update with one gradient
-#   ("drain", mode, lr)                 stateless server step over everything pending
+#   ("drain", mode, lr[, ref, clip])    stateless server step over everything pending; with ref / clip
+#                                       the learning rate is scaled by min(1, ref / K) and every
+#                                       gradient clipped to 2-norm clip (0 = off)
 #   ("snapshot", slot)                  a worker pulls the current weights into a ring slot
 
 DRAIN_SUM = 0
@@ -232,7 +234,8 @@ def scenario_async(seed: int, n_workers: int, batch: int, n_arrivals: int, lr: f
 
 
 def scenario_outage(n_workers: int, batch: int, up_steps: int, down_steps: int, lr: float,
-                    recovery_mode: int = DRAIN_SEQ, recovery_lr: float = None) -> Scenario:
+                    recovery_mode: int = DRAIN_SEQ, recovery_lr: float = None, lr_backlog_ref: float = 0.0,
+                    clip_norm: float = 0.0) -> Scenario:
     """Stateless server: while it is up every round ends with a server step over the W new
     gradients and a publish; while it is down rounds only append; recovery is one server step over
     the whole backlog."""
@@ -243,7 +246,7 @@ def scenario_outage(n_workers: int, batch: int, up_steps: int, down_steps: int, 
         if up:
             ev.append(("drain", DRAIN_SEQ, lr))
             ev.append(("snapshot", 0))
-    ev.append(("drain", recovery_mode, lr if recovery_lr is None else recovery_lr))
+    ev.append(("drain", recovery_mode, lr if recovery_lr is None else recovery_lr, lr_backlog_ref, clip_norm))
     ev.append(("snapshot", 0))
     return Scenario("outage", n_workers, batch, 1, max(n_workers, plan.n_buffered), tuple(ev))
 

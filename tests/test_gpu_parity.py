@@ -178,6 +178,12 @@ def test_config_versions_w64_b128_two_steps(ps):
     _replay_both(ps, synth.scenario_versions(64, 128, 8, 2, 0.01))
 
 
+def test_outage_recovery_with_backlog_lr_and_clipping(ps):
+    """Recovery drain with the learning rate scaled down for the backlog and norm clipping, both modes."""
+    for mode in (synth.DRAIN_SUM, synth.DRAIN_SEQ):
+        _replay_both(ps, synth.scenario_outage(8, 32, 2, 6, 0.01, recovery_mode=mode, lr_backlog_ref=16.0, clip_norm=12.0))
+
+
 # ------------------------------------------------------------------ full-size checks
 
 def test_full_size_round_sampled_workers(ps):
@@ -237,6 +243,49 @@ def test_full_size_drain_1024(ps, mode):
         parity.assert_close(got, ref, parity.WEIGHT_TOL, "drained weights")
         moved = np.abs(ref - theta0).max()
         assert np.abs(got - ref).max() <= 1e-3 * moved
+    finally:
+        ps.ps_destroy(ctx)
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_full_size_mitigated_drain_1024(ps, mode):
+    """The same 3.3 GB backlog drained with backlog-scaled learning rate and norm clipping; rows of
+    three different norms so that some are clipped and some are not."""
+    K, lr, ref, clip = 1024, 0.02, 256.0, 4.0
+    theta0 = synth.he_uniform_theta(3)
+    ctx = ps.ps_init(ps.make_config(1, 1, 1, K, DROP_SEED, P_DROP))
+    try:
+        ps.ps_set_weights(ctx, theta0)
+        ref_theta = theta0.astype(np.float64)
+        total = np.zeros_like(ref_theta)
+        used = orc.backlog_lr(lr, K, ref)
+        assert used == lr / 4
+        n_clipped = 0
+        for k0 in range(0, K, 64):
+            rows = synth.gradient_rows(23, k0, 64, ps.P)
+            rows *= np.array([0.5, 1.0, 2.0], np.float32)[(k0 + np.arange(64)) % 3][:, None]
+            scales = orc.clip_scales(list(rows), clip)
+            n_clipped += sum(s < 1.0 for s in scales)
+            for i in range(64):
+                ps.ps_queue_push_host(ctx, rows[i], 0, 0, k0 + i)
+                g = rows[i].astype(np.float64) * scales[i]
+                if mode == 0:
+                    total += g
+                else:
+                    ref_theta = orc.apply_async(ref_theta, g, used)
+        if mode == 0:
+            ref_theta = ref_theta - used * total
+        assert 0 < n_clipped < K
+        k, lr_used = ps.ps_drain_buffered_mitigated(ctx, mode, lr, ref, clip)
+        assert k == K and abs(lr_used - used) <= 1e-7 * used
+        got = ps.ps_get_weights(ctx)
+        parity.assert_close(got, ref_theta, parity.WEIGHT_TOL, "mitigated drain")
+        assert np.abs(got - ref_theta).max() <= 1e-3 * np.abs(ref_theta - theta0).max()
+        assert ps.ps_version(ctx) == (1 if mode == 0 else K) and ps.ps_queue_meta(ctx) == []
+        for bad in ((-1.0, 0.0), (0.0, -1.0)):
+            with pytest.raises(ps.PsError) as err:
+                ps.ps_drain_buffered_mitigated(ctx, mode, lr, *bad)
+            assert err.value.status == ps.PS_EINVAL
     finally:
         ps.ps_destroy(ctx)
 

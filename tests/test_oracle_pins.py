@@ -411,3 +411,34 @@ def test_forced_decision_equals_the_natural_one_across_a_tie():
     gf, _ = orc.worker_grad(d, theta, xz.reshape(B, 64), y, keep, 0.0,
                             forced=np.array([[0, 1, 5, 2], [0, 1, 21, 2]], np.int32))
     assert np.linalg.norm(gf - gn) <= 1e-9 * max(np.linalg.norm(gn), 1e-3)
+
+
+# ---------------------------------------------------------------- stale-gradient mitigation in the drain
+
+def test_mitigated_drain_closed_forms():
+    rng = np.random.default_rng(3)
+    theta = rng.normal(size=50)
+    pending = [rng.normal(size=50) * s for s in (0.1, 1.0, 5.0, 0.0)]
+    norms = [np.linalg.norm(g) for g in pending]
+    clip = 2.0
+    scales = orc.clip_scales(pending, clip)
+    for g, s, n in zip(pending, scales, norms):
+        assert abs(np.linalg.norm(g * s) - min(n, clip)) < 1e-12          # clipped norm = min(norm, c)
+        assert s == 1.0 if n <= clip else s < 1.0
+    assert orc.clip_scales(pending, 0.0) == [1.0] * 4                      # clipping off
+    # learning rate turned down only beyond the reference backlog
+    assert orc.backlog_lr(0.01, 3, 0.0) == 0.01 and orc.backlog_lr(0.01, 3, 4.0) == 0.01
+    assert orc.backlog_lr(0.01, 8, 4.0) == 0.005
+    for mode in (orc.DRAIN_SUM, orc.DRAIN_SEQ):
+        # both mitigations off: exactly the plain drain
+        t0, used = orc.drain_mitigated(theta, pending, 0.01, mode, 0.0, 0.0)
+        assert used == 0.01 and np.array_equal(t0, orc.drain(theta, pending, 0.01, mode))
+        # backlog scaling alone = plain drain at the reduced rate
+        t1, used = orc.drain_mitigated(theta, pending, 0.01, mode, 2.0, 0.0)
+        assert used == 0.005 and np.array_equal(t1, orc.drain(theta, pending, 0.005, mode))
+        # clipping alone = plain drain of the hand-clipped gradients
+        t2, _ = orc.drain_mitigated(theta, pending, 0.01, mode, 0.0, clip)
+        by_hand = [g if n <= clip else g * (clip / n) for g, n in zip(pending, norms)]
+        assert np.allclose(t2, orc.drain(theta, by_hand, 0.01, mode), rtol=1e-14, atol=1e-16)
+        # the update can never be longer than lr * K * clip
+        assert np.linalg.norm(t2 - theta) <= 0.01 * 4 * clip + 1e-12
