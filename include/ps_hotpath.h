@@ -156,6 +156,24 @@ typedef struct {
 PS_API ps_status ps_drain_buffered_mitigated(ps_ctx* ctx, int32_t mode, const ps_drain_policy* policy,
                                       int32_t* n_applied_host, float* lr_used_host);
 
+/* Recovery of the checkpointing and chain-replication arms (Section 2.1: the resurrected server
+ * rehydrates the latest checkpoint and continues from that older state; Section 2.2: a backup server
+ * with periodically replicated weights takes over): theta := ring[slot], version := the version that
+ * snapshot was taken at, and every pending gradient is dropped (*n_dropped_host, may be NULL,
+ * receives how many).  A checkpoint / replica is a ring slot refreshed with ps_snapshot_weights every
+ * N updates by the caller. */
+PS_API ps_status ps_restore_weights(ps_ctx* ctx, int32_t slot, int32_t* n_dropped_host);
+
+/* Periodic evaluation (Section 3.1: accuracy and loss are collected periodically): inference forward
+ * pass without dropout on n_images images x_dev[n_images][784] with labels y_dev[n_images], using the
+ * server's current weights (slot = -1) or ring slot `slot`.  n_images must be a positive multiple
+ * of batch and at most max_workers * batch.  *loss_host = mean cross-entropy, *accuracy_host =
+ * fraction of images whose arg-max class (lowest index on ties) equals the label, pred_host[n_images]
+ * the predicted classes (each may be NULL).  Waits for the result; overwrites the activations that
+ * ps_debug_last_batch reads. */
+PS_API ps_status ps_evaluate(ps_ctx* ctx, int32_t slot, int32_t n_images, const float* x_dev, const int32_t* y_dev,
+                      double* loss_host, double* accuracy_host, int32_t* pred_host);
+
 /* Copies pending gradient `queue_index` (P floats) to the host. */
 PS_API ps_status ps_get_grad(ps_ctx* ctx, int32_t queue_index, float* grad_host);
 

@@ -186,6 +186,16 @@ def worker_grads(dims: Dims, thetas: np.ndarray, theta_of: Sequence[int], x: np.
     return grads, losses, int(used)
 
 
+def evaluate(dims: Dims, theta: np.ndarray, x: np.ndarray, y: np.ndarray):
+    """Inference forward pass without dropout (Section 3.1: accuracy and loss are evaluated
+    periodically).  Returns (mean loss, accuracy, predicted classes, logits); the predicted class is
+    the lowest index among the largest logits."""
+    n = int(x.shape[0])
+    _, loss, rec = worker_grad(dims, theta, x, y, np.ones((n, dims.F), np.uint8), 0.0, records=True)
+    pred = rec.z.argmax(axis=1).astype(np.int32)
+    return loss, float(np.mean(pred == np.asarray(y))), pred, rec.z
+
+
 # --------------------------------------------------------------------------- update rules
 
 def apply_sync(theta: np.ndarray, grads: Sequence[np.ndarray], lr: float) -> np.ndarray:
@@ -317,6 +327,15 @@ class OracleServer:
         (e,) = self._take([seq])
         self.theta = apply_async(self.theta, e.grad, lr)
         self.version += 1
+
+    def restore_weights(self, slot: int) -> int:
+        """Checkpoint / replica takeover: continue from the older state in `slot`; gradients still
+        pending are lost."""
+        dropped = len(self.pending)
+        self.theta = self.ring[slot].copy()
+        self.version = self.ring_version[slot]
+        self.pending = []
+        return dropped
 
     def drain_buffered(self, mode: int, lr: float, lr_backlog_ref: float = 0.0, clip_norm: float = 0.0) -> int:
         k = len(self.pending)

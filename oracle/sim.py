@@ -11,8 +11,12 @@ from . import oracle as orc
 
 class OracleReplay:
     def __init__(self, scenario, data_seed: int, dropout_seed: int, theta0: np.ndarray, minibatches: Callable,
-                 dropout_p: float = 0.25, dims: orc.Dims = orc.Dims(), n_threads: int = 0):
-        """`minibatches(data_seed, mb_ids, batch)` is the harness's input generator."""
+                 dropout_p: float = 0.25, dims: orc.Dims = orc.Dims(), n_threads: int = 0, eval_batch: Callable = None):
+        """`minibatches(data_seed, mb_ids, batch)` and `eval_batch(data_seed, eval_id, n_images)` are the
+        harness's input generators."""
+        self.eval_batch = eval_batch
+        self.evals: List[tuple] = []         # (eval_id, loss, accuracy, predictions, logits)
+        self.dropped: List[int] = []
         self.sc = scenario
         self.data_seed = data_seed
         self.minibatches = minibatches
@@ -44,6 +48,11 @@ class OracleReplay:
                 sv.drain_buffered(*ev[1:])
             elif kind == "snapshot":
                 sv.snapshot_weights(ev[1])
+            elif kind == "restore":
+                self.dropped.append(sv.restore_weights(ev[1]))
+            elif kind == "eval":
+                x, y = self.eval_batch(self.data_seed, ev[2], ev[1])
+                self.evals.append((ev[2],) + orc.evaluate(sv.dims, sv.theta, x, y))
             else:
                 raise ValueError(kind)
             yield ev, seqs

@@ -27,7 +27,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libps_hotpa
 
 EXPORTS = ["ps_workspace_bytes", "ps_init", "ps_destroy", "ps_sync", "ps_set_weights", "ps_get_weights",
            "ps_snapshot_weights", "worker_grads_batched", "ps_queue_push_host", "ps_apply_sync", "ps_apply_async",
-           "ps_drain_buffered", "ps_drain_buffered_mitigated", "ps_get_grad", "ps_queue_meta", "ps_version", "ps_debug_last_batch", "ps_profile_enable", "ps_profile_read", "ps_profile_kernel_count",
+           "ps_drain_buffered", "ps_drain_buffered_mitigated", "ps_restore_weights", "ps_evaluate", "ps_get_grad", "ps_queue_meta", "ps_version", "ps_debug_last_batch", "ps_profile_enable", "ps_profile_read", "ps_profile_kernel_count",
            "ps_profile_kernel_name", "ps_last_error"]
 
 
@@ -69,6 +69,8 @@ def load_library() -> ctypes.CDLL:
             "ps_drain_buffered": [vp, i32, f32, ctypes.POINTER(i32)],
             "ps_drain_buffered_mitigated": [vp, i32, ctypes.POINTER(ps_drain_policy), ctypes.POINTER(i32),
                                             ctypes.POINTER(f32)],
+            "ps_restore_weights": [vp, i32, ctypes.POINTER(i32)],
+            "ps_evaluate": [vp, i32, i32, vp, vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double), vp],
             "ps_get_grad": [vp, i32, vp],
             "ps_queue_meta": [vp, i32, ctypes.POINTER(i32), vp, vp, vp, vp, vp],
             "ps_version": [vp, ctypes.POINTER(u64)],
@@ -228,6 +230,27 @@ def ps_drain_buffered_mitigated(ctx: Context, mode: int, lr: float, lr_backlog_r
     st = load_library().ps_drain_buffered_mitigated(ctx.handle, mode, ctypes.byref(pol), ctypes.byref(k), ctypes.byref(used))
     _check(ctx, "ps_drain_buffered_mitigated", st)
     return int(k.value), float(used.value)
+
+
+def ps_restore_weights(ctx: Context, slot: int) -> int:
+    """theta := ring[slot]; returns the number of pending gradients that were dropped."""
+    n = ctypes.c_int32(0)
+    _check(ctx, "ps_restore_weights", load_library().ps_restore_weights(ctx.handle, slot, ctypes.byref(n)))
+    return int(n.value)
+
+
+def ps_evaluate(ctx: Context, slot: int, x_dev, y_dev) -> Tuple[float, float, np.ndarray]:
+    """x_dev: torch float32 cuda [n_images, 784]; y_dev: torch int32 cuda [n_images].
+    Returns (mean loss, accuracy, predicted classes)."""
+    n = int(y_dev.numel())
+    assert x_dev.is_cuda and x_dev.is_contiguous() and x_dev.numel() == n * IMAGE_PIXELS
+    assert y_dev.is_cuda and y_dev.is_contiguous()
+    loss, acc = ctypes.c_double(0.0), ctypes.c_double(0.0)
+    pred = np.empty(n, dtype=np.int32)
+    st = load_library().ps_evaluate(ctx.handle, slot, n, ctypes.c_void_p(x_dev.data_ptr()), ctypes.c_void_p(y_dev.data_ptr()),
+                                    ctypes.byref(loss), ctypes.byref(acc), _vp(pred))
+    _check(ctx, "ps_evaluate", st)
+    return float(loss.value), float(acc.value), pred
 
 
 def ps_get_grad(ctx: Context, queue_index: int) -> np.ndarray:

@@ -45,7 +45,7 @@ struct Carve {
 };
 
 struct Layout {
-    uint64_t theta, ring, queue, meta, idx, p1, am1, p2, am2, ht, z, pred, d3, dp2g, part, part1, fpart, normpart, scale, keep, total;
+    uint64_t theta, ring, queue, meta, idx, p1, am1, p2, am2, ht, z, pred, d3, dp2g, part, part1, fpart, normpart, scale, eval_loss, eval_ok, keep, total;
 };
 
 bool config_ok(const ps_config* c)
@@ -78,6 +78,8 @@ Layout make_layout(const ps_config& c)
     l.fpart = k.take((uint64_t)4 * (512 + c.max_workers) * FC2_PART * 4);  // >= n * 4 * fc2_split(n) slots
     l.normpart = k.take((uint64_t)c.queue_capacity * norm_slices() * 4);
     l.scale = k.take((uint64_t)c.queue_capacity * 4);
+    l.eval_loss = k.take(n * 4);
+    l.eval_ok = k.take(n * 4);
     l.keep = k.take((uint64_t)c.batch * FC1);
     l.total = k.off;
     return l;
@@ -445,6 +447,58 @@ ps_status ps_queue_meta(ps_ctx* c, int32_t capacity, int32_t* n_host, uint64_t* 
         if (minibatch_host) minibatch_host[i] = e.mb;
         if (queue_index_host) queue_index_host[i] = q;
     }
+    return PS_OK;
+}
+
+ps_status ps_restore_weights(ps_ctx* c, int32_t slot, int32_t* n_dropped_host)
+{
+    if (!c) return PS_EINVAL;
+    if (slot < 0 || slot >= c->cfg.n_versions) return fail(c, PS_EINVAL, "ps_restore_weights: slot out of range");
+    PS_HIP(c, hipMemcpyAsync(c->theta(), c->ring(slot), sizeof(float) * PSTRIDE, hipMemcpyDeviceToDevice, c->stream));
+    if (n_dropped_host) *n_dropped_host = (int32_t)c->pending.size();
+    const std::vector<int32_t> idx = c->pending;
+    release_entries(c, idx);
+    c->version = c->ring_version[slot];
+    return PS_OK;
+}
+
+ps_status ps_evaluate(ps_ctx* c, int32_t slot, int32_t n_images, const float* x_dev, const int32_t* y_dev,
+                      double* loss_host, double* accuracy_host, int32_t* pred_host)
+{
+    if (!c) return PS_EINVAL;
+    const int B = c->cfg.batch;
+    if (slot < -1 || slot >= c->cfg.n_versions) return fail(c, PS_EINVAL, "ps_evaluate: slot out of range");
+    if (n_images <= 0 || n_images % B != 0 || n_images / B > c->cfg.max_workers)
+        return fail(c, PS_EINVAL, "ps_evaluate: n_images must be a positive multiple of batch, at most max_workers * batch");
+    if (!x_dev || !y_dev || (reinterpret_cast<uintptr_t>(x_dev) & 15) || (reinterpret_cast<uintptr_t>(y_dev) & 3))
+        return fail(c, PS_EINVAL, "ps_evaluate: null or misaligned input");
+    const int n = n_images / B;
+    std::vector<WorkerMeta> meta(n, WorkerMeta{slot, 0, 0, 0});
+    c->last_meta.clear();  // the activations of the last worker call are overwritten
+    ps_status st = upload(c, c->at<WorkerMeta>(c->lay.meta), meta.data(), sizeof(WorkerMeta) * n);
+    if (st != PS_OK) return st;
+    WorkerBuffers wb = buffers(c, n, x_dev, y_dev, nullptr);
+    wb.drop_threshold = 0;  // inference: nothing is dropped, nothing is rescaled
+    wb.drop_scale = 1.f;
+    launch_conv1_fwd(wb, c->stream);
+    launch_conv2_fwd(wb, c->stream);
+    launch_fc1_fwd(wb, c->stream);
+    launch_fc2_eval(wb, c->at<float>(c->lay.eval_loss), c->at<int32_t>(c->lay.eval_ok), c->stream);
+    PS_HIP(c, hipGetLastError());
+    std::vector<float> loss(n_images);
+    std::vector<int32_t> ok(n_images);
+    PS_HIP(c, hipMemcpyAsync(loss.data(), c->at<float>(c->lay.eval_loss), sizeof(float) * n_images, hipMemcpyDeviceToHost, c->stream));
+    PS_HIP(c, hipMemcpyAsync(ok.data(), c->at<int32_t>(c->lay.eval_ok), sizeof(int32_t) * n_images, hipMemcpyDeviceToHost, c->stream));
+    if (pred_host) PS_HIP(c, hipMemcpyAsync(pred_host, c->at<int32_t>(c->lay.pred), sizeof(int32_t) * n_images, hipMemcpyDeviceToHost, c->stream));
+    PS_HIP(c, hipStreamSynchronize(c->stream));
+    double ls = 0.0;
+    int64_t hits = 0;
+    for (int i = 0; i < n_images; ++i) {
+        ls += loss[i];
+        hits += ok[i];
+    }
+    if (loss_host) *loss_host = ls / n_images;
+    if (accuracy_host) *accuracy_host = (double)hits / n_images;
     return PS_OK;
 }
 

@@ -2,6 +2,7 @@
 // parameter layout, per-worker call metadata and the launchers the C ABI drives.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <stddef.h>
 #include <stdint.h>
 
 #include <algorithm>
@@ -60,7 +61,8 @@ struct WorkerBuffers {
 #if defined(__HIPCC__)
 __device__ __forceinline__ const float* worker_theta(const WorkerBuffers& wb, int w)
 {
-    return wb.ring + (size_t)wb.meta[w].slot * PSTRIDE;
+    // slot -1 is the server's current weights, which sit one row before the ring
+    return wb.ring + (ptrdiff_t)wb.meta[w].slot * PSTRIDE;
 }
 __device__ __forceinline__ float* worker_grad(const WorkerBuffers& wb, int w)
 {
@@ -90,6 +92,7 @@ void launch_fc1_fwd(const WorkerBuffers& wb, hipStream_t s);
 void launch_fc1_dw(const WorkerBuffers& wb, hipStream_t s);
 void launch_fc1_dx(const WorkerBuffers& wb, hipStream_t s);
 void launch_fc2(const WorkerBuffers& wb, hipStream_t s);
+void launch_fc2_eval(const WorkerBuffers& wb, float* loss_i, int32_t* correct, hipStream_t s);
 void launch_conv2_fwd(const WorkerBuffers& wb, hipStream_t s);
 void launch_conv2_dx(const WorkerBuffers& wb, hipStream_t s);
 void launch_conv2_dw(const WorkerBuffers& wb, hipStream_t s);

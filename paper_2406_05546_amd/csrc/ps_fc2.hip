@@ -109,7 +109,55 @@ __global__ __launch_bounds__(256) void fc2_kernel(WorkerBuffers wb)
     }
 }
 
+// Inference head (no dropout, no backward): logits, predicted class (lowest index on ties), per-image
+// cross-entropy and whether the prediction equals the label.  One wavefront per image.
+__global__ __launch_bounds__(256) void fc2_eval_kernel(WorkerBuffers wb, float* __restrict__ loss_i,
+                                                       int32_t* __restrict__ correct)
+{
+    const int lane = threadIdx.x & 63;
+    const int g = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (g >= wb.n * wb.B) return;
+    const float* __restrict__ theta = worker_theta(wb, g / wb.B);
+    float hv[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) hv[j] = wb.ht[(size_t)g * FC1 + lane + 64 * j];
+    float z[NCLS];
+#pragma unroll
+    for (int c = 0; c < NCLS; ++c) {
+        float part = 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) part = fmaf(hv[j], theta[OFF_W4 + c * FC1 + lane + 64 * j], part);
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off, 64);
+        z[c] = part + theta[OFF_B4 + c];
+    }
+    const int label = wb.y[g];
+    float zmax = z[0], zy = 0.f, zl = 0.f;
+    int pred = 0;
+#pragma unroll
+    for (int c = 1; c < NCLS; ++c)
+        if (z[c] > zmax) { zmax = z[c]; pred = c; }
+    float se = 0.f;
+#pragma unroll
+    for (int c = 0; c < NCLS; ++c) {
+        se += expf(z[c] - zmax);
+        if (c == label) zy = z[c];
+        if (c == lane) zl = z[c];
+    }
+    if (lane < NCLS) wb.z[(size_t)g * NCLS + lane] = zl;
+    if (lane == 0) {
+        wb.pred[g] = pred;
+        loss_i[g] = zmax + logf(se) - zy;
+        correct[g] = pred == label;
+    }
+}
+
 }  // namespace
+
+void launch_fc2_eval(const WorkerBuffers& wb, float* loss_i, int32_t* correct, hipStream_t s)
+{
+    hipLaunchKernelGGL(fc2_eval_kernel, dim3((wb.n * wb.B + 3) / 4), dim3(256), 0, s, wb, loss_i, correct);
+}
 
 int fc2_split(int n) { return std::min(16, std::max(1, (512 + n - 1) / n)); }
 

@@ -26,6 +26,8 @@ class Replay:
         self.next_seq = 0
         self.meta_log: List[tuple] = []      # (seq, worker, version, mb_id) in arrival order
         self.losses: Dict[int, float] = {}
+        self.evals: List[tuple] = []         # (eval_id, loss, accuracy, predictions)
+        self.dropped: List[int] = []         # pending gradients lost at each restore
 
     def close(self):
         ps.ps_destroy(self.ctx)
@@ -65,6 +67,13 @@ class Replay:
                 self.entry_of.clear()
             elif kind == "snapshot":
                 ps.ps_snapshot_weights(self.ctx, ev[1])
+            elif kind == "restore":
+                self.dropped.append(ps.ps_restore_weights(self.ctx, ev[1]))
+                self.entry_of.clear()
+            elif kind == "eval":
+                x, y = synth.eval_batch(self.data_seed, ev[2], ev[1])
+                xd, yd = torch.from_numpy(x).to(self.device), torch.from_numpy(y).to(self.device)
+                self.evals.append((ev[2],) + ps.ps_evaluate(self.ctx, -1, xd, yd))
             else:
                 raise ValueError(kind)
             yield ev, seqs

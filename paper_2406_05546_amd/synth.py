@@ -181,7 +181,11 @@ class OutagePlan:
 #   ("drain", mode, lr[, ref, clip])    stateless server step over everything pending; with ref / clip
 #                                       the learning rate is scaled by min(1, ref / K) and every
 #                                       gradient clipped to 2-norm clip (0 = off)
-#   ("snapshot", slot)                  a worker pulls the current weights into a ring slot
+#   ("snapshot", slot)                  a worker pulls the current weights into a ring slot (or the
+#                                       server checkpoints / replicates them into it)
+#   ("restore", slot)                   the server is killed and comes back with the weights of that slot;
+#                                       pending gradients are lost
+#   ("eval", n_images, eval_id)         periodic evaluation of the current weights on a held-out batch
 
 DRAIN_SUM = 0
 DRAIN_SEQ = 1
@@ -264,6 +268,46 @@ def scenario_versions(n_workers: int, batch: int, n_slots: int, steps: int, lr: 
         ev.append(("snapshot", step % n_slots))
         seq += n_workers
     return Scenario("versions", n_workers, batch, n_slots, n_workers, tuple(ev))
+
+
+def scenario_checkpoint(n_workers: int, batch: int, steps: int, lr: float, period: int, kills: Sequence[int],
+                        asynchronous: bool = False, eval_images: int = 0, kills_inflight: Sequence[int] = ()) -> Scenario:
+    """Checkpointing / chain-replication arm: sync (or async in worker order) training in which the
+    weights are copied to a checkpoint slot (a file in the checkpointing arms, the backup server's
+    memory in the chain arms) after every `period` weight updates; after each step listed in `kills`
+    the server dies and comes back with the checkpointed weights, and the workers pull them; in a
+    step listed in `kills_inflight` it dies while that step's gradients are still pending, which are
+    lost.  With eval_images > 0 the weights are evaluated after every step."""
+    ckpt = 1
+    ev, seq, updates = [("snapshot", ckpt)], 0, 0
+    for step in range(steps):
+        ws = list(range(n_workers))
+        ev.append(("grads", ws, [0] * n_workers, [minibatch_id(w, step) for w in ws]))
+        if step in kills_inflight:
+            ev.append(("restore", ckpt))
+        elif asynchronous:
+            for i in range(n_workers):
+                ev.append(("async", seq + i, lr))
+                updates += 1
+                if updates % period == 0:
+                    ev.append(("snapshot", ckpt))
+        else:
+            ev.append(("sync", list(range(seq, seq + n_workers)), lr))
+            updates += 1
+            if updates % period == 0:
+                ev.append(("snapshot", ckpt))
+        seq += n_workers
+        if step in kills:
+            ev.append(("restore", ckpt))
+        ev.append(("snapshot", 0))
+        if eval_images:
+            ev.append(("eval", eval_images, step))
+    return Scenario("checkpoint", n_workers, batch, 2, n_workers, tuple(ev))
+
+
+def eval_batch(seed: int, eval_id: int, n_images: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Held-out evaluation images: a minibatch id space no worker uses."""
+    return minibatch(seed, minibatch_id(0xFFFFFFFF, eval_id), n_images)
 
 
 def paper_configs() -> dict:

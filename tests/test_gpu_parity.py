@@ -114,7 +114,8 @@ def _replay_both(ps, sc, check_every=1, n_threads=0, tie_tol=1e-4):
     compared (every `check_every`-th arrival), at the end the weights and the queue metadata."""
     from paper_2406_05546_amd.replay import Replay
     theta0 = synth.he_uniform_theta(DATA_SEED)
-    o = OracleReplay(sc, DATA_SEED, DROP_SEED, theta0, synth.minibatches, P_DROP, n_threads=n_threads)
+    o = OracleReplay(sc, DATA_SEED, DROP_SEED, theta0, synth.minibatches, P_DROP, n_threads=n_threads,
+                     eval_batch=synth.eval_batch)
     g = Replay(sc, DATA_SEED, DROP_SEED, theta0, P_DROP)
     stats = {"worst": 0.0, "checked": 0, "tie_workers": 0, "forced": 0}
     t0 = time.time()
@@ -146,6 +147,12 @@ def _replay_both(ps, sc, check_every=1, n_threads=0, tie_tol=1e-4):
                     o.last[s].grad[:] = r["grad"]
                 assert abs(g.losses[s] - o.losses[s]) <= 2e-5 * abs(o.losses[s])
         theta_gpu, theta_ref = g.weights(), o.server.theta
+        assert g.dropped == o.dropped and len(g.evals) == len(o.evals)
+        for (gid, gl, ga, gp), (oid, ol, oa, op, oz) in zip(g.evals, o.evals):
+            zs = np.sort(oz, axis=1)
+            clear = (zs[:, -1] - zs[:, -2]) > 1e-4
+            assert gid == oid and abs(gl - ol) <= 2e-5 * abs(ol) and np.array_equal(gp[clear], op[clear])
+            assert abs(ga - oa) <= float(np.mean(~clear)) + 1e-12
         assert g.meta_log == o.meta_log, f"{sc.name}: queue metadata / arrival order differs"
         assert ps.ps_queue_meta(g.ctx) == [] and ps.ps_version(g.ctx) == o.server.version
         errs = parity.assert_close(theta_gpu, theta_ref, parity.WEIGHT_TOL, f"{sc.name} final weights")
@@ -182,6 +189,51 @@ def test_outage_recovery_with_backlog_lr_and_clipping(ps):
     """Recovery drain with the learning rate scaled down for the backlog and norm clipping, both modes."""
     for mode in (synth.DRAIN_SUM, synth.DRAIN_SEQ):
         _replay_both(ps, synth.scenario_outage(8, 32, 2, 6, 0.01, recovery_mode=mode, lr_backlog_ref=16.0, clip_norm=12.0))
+
+
+def test_checkpoint_and_chain_arms_with_evaluation(ps):
+    """Sync and async training with periodic checkpoints / replication, one kill after a step and one
+    with gradients in flight, evaluated after every step."""
+    for asynchronous in (False, True):
+        _replay_both(ps, synth.scenario_checkpoint(4, 32, 8, 0.01, period=3, kills=[4], asynchronous=asynchronous,
+                                                   eval_images=128, kills_inflight=[6]))
+
+
+def test_evaluate_full_size_and_slots(ps):
+    """65,536 images in one evaluation call; the oracle checks a sample of them; ring slots and errors."""
+    W, B = 256, 256
+    theta0 = synth.he_uniform_theta(DATA_SEED)
+    x, y = synth.eval_batch(DATA_SEED, 0, W * B)
+    ctx = ps.ps_init(ps.make_config(W, B, 2, 1, DROP_SEED, P_DROP))
+    try:
+        ps.ps_set_weights(ctx, theta0)
+        xd, yd = _torch_inputs(x, y)
+        loss, acc, pred = ps.ps_evaluate(ctx, -1, xd, yd)
+        sample = np.r_[0:64, 30000:30064, W * B - 64:W * B]
+        l_ref, _, p_ref, z_ref = orc.evaluate(orc.Dims(), theta0.astype(np.float64), x[sample], y[sample])
+        zs = np.sort(z_ref, axis=1)
+        clear = (zs[:, -1] - zs[:, -2]) > 1e-4
+        assert np.array_equal(pred[sample][clear], p_ref[clear]) and clear.mean() > 0.99
+        assert abs(acc - float(np.mean(pred == y))) < 1e-12 and 0.05 < acc < 0.15        # random labels
+        assert abs(loss - l_ref) < 0.1 and np.isfinite(loss)
+        # a ring slot holds different weights
+        theta1 = synth.he_uniform_theta(DATA_SEED + 1)
+        g = ps.ps_queue_push_host(ctx, (theta0 - theta1).astype(np.float32), 0, 0, 0)
+        ps.ps_apply_async(ctx, g, 1.0)
+        small_x, small_y = _torch_inputs(x[:B].copy(), y[:B].copy())
+        l_cur, _, _ = ps.ps_evaluate(ctx, -1, small_x, small_y)
+        l_old, _, _ = ps.ps_evaluate(ctx, 0, small_x, small_y)
+        r_cur = orc.evaluate(orc.Dims(), ps.ps_get_weights(ctx).astype(np.float64), x[:B], y[:B])[0]
+        r_old = orc.evaluate(orc.Dims(), theta0.astype(np.float64), x[:B], y[:B])[0]
+        assert abs(l_cur - r_cur) <= 2e-5 * r_cur and abs(l_old - r_old) <= 2e-5 * r_old and abs(r_cur - r_old) > 1e-3
+        odd_x, odd_y = _torch_inputs(x[:B + 1].copy(), y[:B + 1].copy())
+        for call in (lambda: ps.ps_evaluate(ctx, 2, small_x, small_y), lambda: ps.ps_evaluate(ctx, -1, odd_x, odd_y),
+                     lambda: ps.ps_restore_weights(ctx, 2)):
+            with pytest.raises(ps.PsError) as err:
+                call()
+            assert err.value.status == ps.PS_EINVAL
+    finally:
+        ps.ps_destroy(ctx)
 
 
 # ------------------------------------------------------------------ full-size checks

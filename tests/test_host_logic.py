@@ -15,7 +15,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "ps_hotpath.h")).read()
     declared = re.findall(r"^PS_API\s+[\w\s\*]+?\b(\w+)\(", header, flags=re.M)
-    assert sorted(declared) == sorted(ps.EXPORTS) and len(declared) == 22
+    assert sorted(declared) == sorted(ps.EXPORTS) and len(declared) == 24
     lib = ps.load_library()
     for name in declared:
         assert getattr(lib, name) is not None
@@ -97,3 +97,16 @@ def test_outage_scenario_shape():
     v = synth.paper_configs()["versions_w64_b128"]
     assert v.n_slots == 8 and v.n_gradients == 3200
     assert [e[2] for e in v.events if e[0] == "grads"][0][:10] == [0, 1, 2, 3, 4, 5, 6, 7, 0, 1]
+
+
+def test_checkpoint_scenario_shape():
+    sc = synth.scenario_checkpoint(2, 8, 6, 0.01, period=2, kills=[3], eval_images=16, kills_inflight=[4])
+    kinds = [e[0] for e in sc.events]
+    assert kinds.count("restore") == 2 and kinds.count("eval") == 6 and kinds.count("grads") == 6
+    assert kinds.count("sync") == 5                       # the in-flight step is never applied
+    assert sc.n_slots == 2 and sc.max_call == 2
+    # checkpoints after updates 2 and 4 (and the initial one)
+    assert [e for e in sc.events if e == ("snapshot", 1)].__len__() == 3
+    x, y = synth.eval_batch(5, 0, 16)
+    xw, _ = synth.minibatch(5, synth.minibatch_id(0, 0), 16)
+    assert x.shape == (16, 784) and not np.array_equal(x, xw)

@@ -442,3 +442,37 @@ def test_mitigated_drain_closed_forms():
         assert np.allclose(t2, orc.drain(theta, by_hand, 0.01, mode), rtol=1e-14, atol=1e-16)
         # the update can never be longer than lr * K * clip
         assert np.linalg.norm(t2 - theta) <= 0.01 * 4 * clip + 1e-12
+
+
+# ---------------------------------------------------------------- evaluation and checkpoint recovery
+
+def test_evaluate_matches_independent_forward():
+    d, n = orc.Dims(), 6
+    x, y = synth.minibatch(4, 9, n)
+    theta = synth.he_uniform_theta(4).astype(float) + np.random.default_rng(2).uniform(-0.02, 0.02, d.P)
+    loss, acc, pred, z = orc.evaluate(d, theta, x, y)
+    _, tloss, tz = _torch_grad(d, theta, x, y, np.ones((n, d.F)), 0.0)          # no dropout, scale 1
+    assert abs(loss - tloss) <= 1e-12 * abs(tloss) and np.allclose(z, tz, rtol=1e-11, atol=1e-12)
+    assert np.array_equal(pred, tz.argmax(1)) and acc == float(np.mean(tz.argmax(1) == y))
+    # lowest index wins a tie: zero weights give all-equal logits
+    _, acc0, pred0, _ = orc.evaluate(d, np.zeros(d.P), x, np.zeros(n, np.int32))
+    assert (pred0 == 0).all() and acc0 == 1.0
+
+
+def test_restore_continues_from_the_checkpointed_state():
+    sc = synth.scenario_checkpoint(2, 4, 5, 0.05, period=2, kills=[2], kills_inflight=[4])
+    nd = synth.NetDims(8, 8, 2, 3, 8, 3)
+    theta0 = synth.he_uniform_theta(3, nd)
+    mb = lambda seed, ids, B: synth.minibatches(seed, ids, B, h=8, w=8, n_classes=3)
+    from oracle.sim import OracleReplay
+    o = OracleReplay(sc, 3, 7, theta0, mb, 0.25, dims=TINY)
+    seen = []
+    for ev, _ in o.steps():
+        if ev[0] == "snapshot" and ev[1] == 1:
+            ckpt = (o.server.theta.copy(), o.server.version)
+        if ev[0] == "restore":
+            assert np.array_equal(o.server.theta, ckpt[0]) and o.server.version == ckpt[1] and not o.server.pending
+            seen.append(o.dropped[-1])
+    assert seen == [0, 2]                                   # the in-flight kill loses that step's two gradients
+    # updates 1,2 -> checkpoint; update 3, kill -> back to 2; update -> 3, checkpoint; in-flight kill -> 3
+    assert o.server.version == 3
