@@ -34,16 +34,16 @@ template <int COUNT, int CHS>
 struct Pool1Stage {
     static constexpr int P1_IMS = C1 * CHS;
     static constexpr int N4 = COUNT * (P1_SIZE / 4), NV = (N4 + 255) / 256;
-    float4 v[NV];
-    // images [g0, g0 + valid) exist; the rest of the group is staged as zeros
+    floatx4 v[NV];
+    // images [g0, g0 + valid) exist; the rest of the group repeats the last existing image (its
+    // results are never stored), so the loads need no branches
     __device__ __forceinline__ void prefetch(const float* __restrict__ p1, size_t g0, int valid, int tid)
     {
 #pragma unroll
         for (int k = 0; k < NV; ++k) {
-            const int i4 = tid + 256 * k;
-            v[k] = (i4 < N4 && i4 / (P1_SIZE / 4) < valid)
-                       ? *reinterpret_cast<const float4*>(p1 + g0 * P1_SIZE + (size_t)i4 * 4)
-                       : make_float4(0.f, 0.f, 0.f, 0.f);
+            const int i4 = min(tid + 256 * k, N4 - 1);
+            const int img = min(i4 / (P1_SIZE / 4), valid - 1);
+            v[k] = *reinterpret_cast<const floatx4*>(p1 + (g0 + img) * P1_SIZE + (size_t)(i4 % (P1_SIZE / 4)) * 4);
         }
     }
     __device__ __forceinline__ void commit(float* __restrict__ tile, int tid) const
@@ -51,12 +51,12 @@ struct Pool1Stage {
 #pragma unroll
         for (int k = 0; k < NV; ++k) {
             const int i4 = tid + 256 * k;
-            if (i4 >= N4) break;
             const int img = i4 / (P1_SIZE / 4), r = (i4 % (P1_SIZE / 4)) * 4, c = r / P1_POS, pos = r % P1_POS;
             float* plane = tile + img * P1_IMS + c * CHS + 17;  // (1,1)
-            const float e[4] = {v[k].x, v[k].y, v[k].z, v[k].w};
+            if (256 * (k + 1) <= N4 || i4 < N4) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) plane[((pos + j) / P1_W) * 16 + (pos + j) % P1_W] = e[j];
+                for (int j = 0; j < 4; ++j) plane[((pos + j) / P1_W) * 16 + (pos + j) % P1_W] = v[k][j];
+            }
         }
     }
 };
