@@ -174,6 +174,75 @@ PS_API ps_status ps_restore_weights(ps_ctx* ctx, int32_t slot, int32_t* n_droppe
 PS_API ps_status ps_evaluate(ps_ctx* ctx, int32_t slot, int32_t n_images, const float* x_dev, const int32_t* y_dev,
                       double* loss_host, double* accuracy_host, int32_t* pred_host);
 
+/* ---- Lock-free gradient store: workers and server on two streams -------------------------------
+ *
+ * Section 3.3 (last paragraph) observes that accesses to the gradient store can be lock-free, since a
+ * gradient is written once by its worker and read, then deleted, by the server; the implementation
+ * measured in the paper takes a lock instead, and the Future Work section lists a better mechanism.
+ * Here the store's state lives in device memory.  Workers (the stream given to ps_init) and the
+ * server (a second stream the context creates, same priority) run concurrently and meet only there:
+ * a batch of workers claims consecutive positions with one atomic add, writes its gradient rows and
+ * then stamps them as complete; a server step takes the longest prefix of complete rows not yet
+ * consumed, applies it in position order and deletes it by advancing the consumed count.  Positions
+ * count appended gradients from 0 and never wrap; position p uses queue row p % queue_capacity.
+ *
+ * While the store holds gradients that the host has not yet seen consumed (ps_store_state tells),
+ * the calls above that touch the queue or the server's weights return PS_ESTATE; the store calls in
+ * turn need the pending queue of those calls to be empty.  Version counts and snapshot versions carry
+ * over in both directions.  ps_get_weights, ps_evaluate and ps_sync wait for both streams. */
+
+typedef struct {
+    uint64_t claimed;   /* gradients ever appended (positions handed out)               */
+    uint64_t published; /* length of the prefix of them whose rows are completely written */
+    uint64_t consumed;  /* gradients ever applied and deleted                            */
+    uint64_t version;   /* weight updates applied so far                                 */
+    uint64_t steps;     /* server steps so far that applied at least one gradient        */
+} ps_store_counters;
+
+typedef struct {
+    uint64_t first;         /* first position the step consumed */
+    uint32_t count;         /* how many, consecutive            */
+    uint32_t mode;          /* ps_drain_mode                    */
+    uint64_t version_after; /* version once it was applied      */
+} ps_store_step;
+
+/* Worker step as worker_grads_batched, but the queue rows are claimed on the device and nothing
+ * about them comes back to the host: the n gradients take positions claimed .. claimed + n - 1 in
+ * array order.  Waits (on the device, not the host) for the last ps_store_publish into each ring slot
+ * it reads.  PS_EFULL if claimed + n - consumed could exceed queue_capacity by what the host has seen
+ * so far (it looks again, waiting for the server stream, before giving up); PS_ESTATE if the ordered
+ * queue above is not empty. */
+PS_API ps_status worker_grads_append(ps_ctx* ctx, int32_t n, const int32_t* worker_id_host,
+                                     const int32_t* version_slot_host, const uint64_t* minibatch_id_host,
+                                     const float* x_dev, const int32_t* y_dev, float* loss_dev);
+
+/* Server step on the server stream: takes the rows that are complete when the step runs, at most
+ * max_entries of them (0 = no limit), applies them as one update with their sum (PS_DRAIN_SUM,
+ * version += 1) or one update each in position order (PS_DRAIN_SEQ, version += count), and deletes
+ * them.  Nothing complete: nothing changes.  With wait_for_workers != 0 the step first waits, on the
+ * device, for every worker_grads_append enqueued so far, so that it takes all of those (up to the
+ * limit); with 0 it races the workers and how many it takes depends on timing (ps_store_steps
+ * tells afterwards). */
+PS_API ps_status ps_store_consume(ps_ctx* ctx, int32_t mode, float lr, int32_t max_entries, int32_t wait_for_workers);
+
+/* ring[slot] := the server's weights, on the server stream, after the server steps enqueued so far
+ * and after every enqueued worker step that reads the slot; the slot's version is recorded on the
+ * device.  The lock-free counterpart of ps_snapshot_weights. */
+PS_API ps_status ps_store_publish(ps_ctx* ctx, int32_t slot);
+
+/* Waits for both streams and reads the counters.  Once consumed == claimed the ordered calls above
+ * are available again. */
+PS_API ps_status ps_store_state(ps_ctx* ctx, ps_store_counters* counters_host);
+
+/* Waits for both streams; the most recent server steps that applied something, oldest first: *n_host
+ * receives how many are returned (at most `capacity`, at most the 1024 the device keeps). */
+PS_API ps_status ps_store_steps(ps_ctx* ctx, int32_t capacity, int32_t* n_host, ps_store_step* steps_host);
+
+/* Waits for both streams; copies the gradient at `position` (P floats) and its metadata (each pointer
+ * may be NULL).  PS_ESTATE unless consumed <= position < published. */
+PS_API ps_status ps_store_entry(ps_ctx* ctx, uint64_t position, float* grad_host, int32_t* worker_host,
+                                uint64_t* version_host, uint64_t* minibatch_host);
+
 /* Copies pending gradient `queue_index` (P floats) to the host. */
 PS_API ps_status ps_get_grad(ps_ctx* ctx, int32_t queue_index, float* grad_host);
 

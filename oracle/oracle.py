@@ -328,6 +328,21 @@ class OracleServer:
         self.theta = apply_async(self.theta, e.grad, lr)
         self.version += 1
 
+    def consume(self, mode: int, lr: float, k: int) -> int:
+        """Server step of the lock-free gradient store (Section 3.3, last paragraph: a gradient is
+        written once, read once by the server and then deleted): the first k pending gradients, in
+        arrival order, are applied as one summed update or as k successive updates, and removed."""
+        k = min(k, len(self.pending))
+        if k == 0:
+            return 0
+        seqs = [e.seq for e in self.pending[:k]]
+        if mode == DRAIN_SUM:
+            self.apply_sync(seqs, lr)
+        else:
+            for s in seqs:
+                self.apply_async(s, lr)
+        return k
+
     def restore_weights(self, slot: int) -> int:
         """Checkpoint / replica takeover: continue from the older state in `slot`; gradients still
         pending are lost."""

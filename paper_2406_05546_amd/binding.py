@@ -27,8 +27,10 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libps_hotpa
 
 EXPORTS = ["ps_workspace_bytes", "ps_init", "ps_destroy", "ps_sync", "ps_set_weights", "ps_get_weights",
            "ps_snapshot_weights", "worker_grads_batched", "ps_queue_push_host", "ps_apply_sync", "ps_apply_async",
-           "ps_drain_buffered", "ps_drain_buffered_mitigated", "ps_restore_weights", "ps_evaluate", "ps_get_grad", "ps_queue_meta", "ps_version", "ps_debug_last_batch", "ps_profile_enable", "ps_profile_read", "ps_profile_kernel_count",
-           "ps_profile_kernel_name", "ps_last_error"]
+           "ps_drain_buffered", "ps_drain_buffered_mitigated", "ps_restore_weights", "ps_evaluate",
+           "worker_grads_append", "ps_store_consume", "ps_store_publish", "ps_store_state", "ps_store_steps",
+           "ps_store_entry", "ps_get_grad", "ps_queue_meta", "ps_version", "ps_debug_last_batch", "ps_profile_enable",
+           "ps_profile_read", "ps_profile_kernel_count", "ps_profile_kernel_name", "ps_last_error"]
 
 
 class PsError(RuntimeError):
@@ -39,6 +41,16 @@ class PsError(RuntimeError):
 
 class ps_drain_policy(ctypes.Structure):
     _fields_ = [("lr", ctypes.c_float), ("lr_backlog_ref", ctypes.c_float), ("clip_norm", ctypes.c_float)]
+
+
+class ps_store_counters(ctypes.Structure):
+    _fields_ = [("claimed", ctypes.c_uint64), ("published", ctypes.c_uint64), ("consumed", ctypes.c_uint64),
+                ("version", ctypes.c_uint64), ("steps", ctypes.c_uint64)]
+
+
+class ps_store_step(ctypes.Structure):
+    _fields_ = [("first", ctypes.c_uint64), ("count", ctypes.c_uint32), ("mode", ctypes.c_uint32),
+                ("version_after", ctypes.c_uint64)]
 
 
 class ps_config(ctypes.Structure):
@@ -71,6 +83,12 @@ def load_library() -> ctypes.CDLL:
                                             ctypes.POINTER(f32)],
             "ps_restore_weights": [vp, i32, ctypes.POINTER(i32)],
             "ps_evaluate": [vp, i32, i32, vp, vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double), vp],
+            "worker_grads_append": [vp, i32, vp, vp, vp, vp, vp, vp],
+            "ps_store_consume": [vp, i32, f32, i32, i32],
+            "ps_store_publish": [vp, i32],
+            "ps_store_state": [vp, ctypes.POINTER(ps_store_counters)],
+            "ps_store_steps": [vp, i32, ctypes.POINTER(i32), ctypes.POINTER(ps_store_step)],
+            "ps_store_entry": [vp, u64, vp, ctypes.POINTER(i32), ctypes.POINTER(u64), ctypes.POINTER(u64)],
             "ps_get_grad": [vp, i32, vp],
             "ps_queue_meta": [vp, i32, ctypes.POINTER(i32), vp, vp, vp, vp, vp],
             "ps_version": [vp, ctypes.POINTER(u64)],
@@ -251,6 +269,60 @@ def ps_evaluate(ctx: Context, slot: int, x_dev, y_dev) -> Tuple[float, float, np
                                     ctypes.byref(loss), ctypes.byref(acc), _vp(pred))
     _check(ctx, "ps_evaluate", st)
     return float(loss.value), float(acc.value), pred
+
+
+def worker_grads_append(ctx: Context, worker_id: Sequence[int], version_slot: Sequence[int],
+                        minibatch_id: Sequence[int], x_dev, y_dev, loss_dev=None) -> None:
+    """As worker_grads_batched, into the lock-free store: positions are claimed on the device."""
+    n = len(worker_id)
+    w = _np(worker_id, np.int32)
+    s = _np(version_slot, np.int32)
+    m = _np(minibatch_id, np.uint64)
+    assert w.shape == s.shape == m.shape == (n,)
+    if n:
+        import torch
+        B = ctx.cfg.batch
+        assert x_dev.is_cuda and x_dev.dtype == torch.float32 and x_dev.is_contiguous()
+        assert y_dev.is_cuda and y_dev.dtype == torch.int32 and y_dev.is_contiguous()
+        assert x_dev.numel() >= n * B * IMAGE_PIXELS and y_dev.numel() >= n * B
+        assert loss_dev is None or (loss_dev.is_cuda and loss_dev.dtype == torch.float32 and loss_dev.numel() >= n)
+    st = load_library().worker_grads_append(
+        ctx.handle, n, _vp(w), _vp(s), _vp(m),
+        ctypes.c_void_p(x_dev.data_ptr()) if n else None, ctypes.c_void_p(y_dev.data_ptr()) if n else None,
+        ctypes.c_void_p(loss_dev.data_ptr()) if loss_dev is not None else None)
+    _check(ctx, "worker_grads_append", st)
+
+
+def ps_store_consume(ctx: Context, mode: int, lr: float, max_entries: int = 0, wait_for_workers: bool = True) -> None:
+    st = load_library().ps_store_consume(ctx.handle, mode, lr, max_entries, 1 if wait_for_workers else 0)
+    _check(ctx, "ps_store_consume", st)
+
+
+def ps_store_publish(ctx: Context, slot: int) -> None:
+    _check(ctx, "ps_store_publish", load_library().ps_store_publish(ctx.handle, slot))
+
+
+def ps_store_state(ctx: Context) -> dict:
+    c = ps_store_counters()
+    _check(ctx, "ps_store_state", load_library().ps_store_state(ctx.handle, ctypes.byref(c)))
+    return {k: int(getattr(c, k)) for k, _ in ps_store_counters._fields_}
+
+
+def ps_store_steps(ctx: Context, capacity: int = 1024) -> List[Tuple[int, int, int, int]]:
+    """Server steps that applied something, oldest first, as (first position, count, mode, version after)."""
+    n = ctypes.c_int32(0)
+    buf = (ps_store_step * max(capacity, 1))()
+    _check(ctx, "ps_store_steps", load_library().ps_store_steps(ctx.handle, capacity, ctypes.byref(n), buf))
+    return [(int(buf[i].first), int(buf[i].count), int(buf[i].mode), int(buf[i].version_after)) for i in range(n.value)]
+
+
+def ps_store_entry(ctx: Context, position: int, want_grad: bool = True) -> Tuple[Optional[np.ndarray], int, int, int]:
+    """(gradient or None, worker id, version of the snapshot used, minibatch id) of an unconsumed position."""
+    g = np.empty(P, dtype=np.float32) if want_grad else None
+    w, v, m = ctypes.c_int32(0), ctypes.c_uint64(0), ctypes.c_uint64(0)
+    st = load_library().ps_store_entry(ctx.handle, position, _vp(g), ctypes.byref(w), ctypes.byref(v), ctypes.byref(m))
+    _check(ctx, "ps_store_entry", st)
+    return g, int(w.value), int(v.value), int(m.value)
 
 
 def ps_get_grad(ctx: Context, queue_index: int) -> np.ndarray:

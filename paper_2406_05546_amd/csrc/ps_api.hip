@@ -21,6 +21,7 @@ static_assert(PS_PARAM_COUNT == P, "header and kernels disagree on the parameter
 namespace {
 
 constexpr int N_STAGE = 4;  // pinned host staging buffers for per-call index / metadata uploads
+constexpr int N_HEADRB = 8;  // read-backs of the store's consumed count in flight
 
 struct Entry {
     bool pending = false;
@@ -30,6 +31,11 @@ struct Entry {
 
 struct Stage {
     void* host = nullptr;
+    hipEvent_t done = nullptr;
+    bool in_flight = false;
+};
+
+struct HeadReadback {
     hipEvent_t done = nullptr;
     bool in_flight = false;
 };
@@ -45,7 +51,7 @@ struct Carve {
 };
 
 struct Layout {
-    uint64_t theta, ring, queue, meta, idx, p1, am1, p2, am2, ht, z, pred, d3, dp2g, part, part1, fpart, normpart, scale, eval_loss, eval_ok, keep, total;
+    uint64_t theta, ring, queue, meta, idx, st_state, st_stamp, st_entry, st_ringver, st_log, st_range, st_idx, st_wid, p1, am1, p2, am2, ht, z, pred, d3, dp2g, part, part1, fpart, normpart, scale, eval_loss, eval_ok, keep, total;
 };
 
 bool config_ok(const ps_config* c)
@@ -64,6 +70,14 @@ Layout make_layout(const ps_config& c)
     l.queue = k.take(row * c.queue_capacity);
     l.meta = k.take(sizeof(WorkerMeta) * c.max_workers);
     l.idx = k.take(sizeof(int32_t) * c.queue_capacity);
+    l.st_state = k.take(sizeof(StoreState));
+    l.st_stamp = k.take(sizeof(unsigned long long) * c.queue_capacity);
+    l.st_entry = k.take(sizeof(StoreEntryMeta) * c.queue_capacity);
+    l.st_ringver = k.take(sizeof(unsigned long long) * c.n_versions);
+    l.st_log = k.take(sizeof(StoreLogRec) * STORE_LOG_CAP);
+    l.st_range = k.take(sizeof(StoreRange));
+    l.st_idx = k.take(sizeof(int32_t) * c.queue_capacity);
+    l.st_wid = k.take(sizeof(int32_t) * c.max_workers);
     l.p1 = k.take(n * P1_SIZE * 4);
     l.am1 = k.take(n * P1_SIZE);
     l.p2 = k.take(n * P2_SIZE * 4);
@@ -103,6 +117,18 @@ struct ps_ctx {
     size_t stage_bytes = 0;
     Profiler prof;
     std::string err;
+
+    // Lock-free store: the server stream, and what the host knows of the device-side counters.
+    hipStream_t server = nullptr;
+    hipEvent_t ev_join = nullptr, ev_workers = nullptr;
+    std::vector<hipEvent_t> ev_slot_read, ev_slot_written;  // last worker read of / server write to a ring slot
+    std::vector<char> slot_read_valid, slot_written_valid;
+    uint64_t store_claimed = 0, store_confirmed = 0;  // exact; lower bound of the consumed count
+    bool store_synced = false;   // device-side version counters hold the host's values
+    bool server_dirty = false;   // the server stream was given work the worker stream has not waited for
+    unsigned long long* headrb_host = nullptr;  // pinned, [N_HEADRB]
+    HeadReadback headrb[N_HEADRB];
+    int next_headrb = 0;
 
     template <class T>
     T* at(uint64_t off) const { return reinterpret_cast<T*>(ws + off); }
@@ -206,6 +232,84 @@ WorkerBuffers buffers(const ps_ctx* c, int n, const float* x, const int32_t* y, 
     return wb;
 }
 
+StoreBuffers store_buffers(const ps_ctx* c)
+{
+    StoreBuffers sb{};
+    sb.state = c->at<StoreState>(c->lay.st_state);
+    sb.stamp = c->at<unsigned long long>(c->lay.st_stamp);
+    sb.entry = c->at<StoreEntryMeta>(c->lay.st_entry);
+    sb.ring_version = c->at<unsigned long long>(c->lay.st_ringver);
+    sb.log = c->at<StoreLogRec>(c->lay.st_log);
+    sb.range = c->at<StoreRange>(c->lay.st_range);
+    sb.idx = c->at<int32_t>(c->lay.st_idx);
+    sb.worker_id = c->at<int32_t>(c->lay.st_wid);
+    sb.cap = c->cfg.queue_capacity;
+    return sb;
+}
+
+// Whatever the server stream has been given so far precedes what the worker stream is given next.
+ps_status workers_wait_server(ps_ctx* c)
+{
+    if (!c->server_dirty) return PS_OK;
+    PS_HIP(c, hipEventRecord(c->ev_join, c->server));
+    PS_HIP(c, hipStreamWaitEvent(c->stream, c->ev_join, 0));
+    c->server_dirty = false;
+    return PS_OK;
+}
+
+ps_status server_waits_workers(ps_ctx* c)
+{
+    PS_HIP(c, hipEventRecord(c->ev_workers, c->stream));
+    PS_HIP(c, hipStreamWaitEvent(c->server, c->ev_workers, 0));
+    return PS_OK;
+}
+
+// Folds finished read-backs of the consumed count into the host's lower bound; never blocks.
+void poll_consumed(ps_ctx* c)
+{
+    for (int i = 0; i < N_HEADRB; ++i) {
+        HeadReadback& r = c->headrb[i];
+        if (r.in_flight && hipEventQuery(r.done) == hipSuccess) {
+            c->store_confirmed = std::max<uint64_t>(c->store_confirmed, c->headrb_host[i]);
+            r.in_flight = false;
+        }
+    }
+}
+
+bool store_open(ps_ctx* c)
+{
+    if (c->store_claimed != c->store_confirmed) poll_consumed(c);
+    return c->store_claimed != c->store_confirmed;
+}
+
+// Entry check of the calls that work on the ordered queue or the server's weights from the worker
+// stream: not while the store holds gradients; ordered after the server stream's work.
+ps_status ordered_guard(ps_ctx* c, const char* who)
+{
+    if (store_open(c))
+        return fail(c, PS_ESTATE, std::string(who) + ": the lock-free store holds gradients not yet seen consumed "
+                                                     "(consume them, then ps_store_state)");
+    c->store_synced = false;
+    return workers_wait_server(c);
+}
+
+// First store call after ordered calls: hand the version counters to the device.
+ps_status store_begin(ps_ctx* c, const char* who)
+{
+    if (c->store_synced) return PS_OK;
+    if (!c->pending.empty()) return fail(c, PS_ESTATE, std::string(who) + ": the ordered queue is not empty");
+    ps_status st = workers_wait_server(c);
+    if (st != PS_OK) return st;
+    const StoreBuffers sb = store_buffers(c);
+    PS_HIP(c, launch_store_reset(sb, c->version, c->stream));
+    st = upload(c, sb.ring_version, c->ring_version.data(), sizeof(uint64_t) * c->ring_version.size());
+    if (st != PS_OK) return st;
+    st = server_waits_workers(c);
+    if (st != PS_OK) return st;
+    c->store_synced = true;
+    return PS_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -233,8 +337,21 @@ ps_status ps_init(ps_ctx** out, const ps_config* cfg, void* workspace_dev, uint6
     c->entries.assign(cfg->queue_capacity, Entry{});
     for (int32_t q = cfg->queue_capacity - 1; q >= 0; --q) c->free_list.push_back(q);
     c->ring_version.assign(cfg->n_versions, 0);
-    c->stage_bytes = std::max(sizeof(WorkerMeta) * (size_t)cfg->max_workers, sizeof(int32_t) * (size_t)cfg->queue_capacity);
-    hipError_t e = hipSuccess;
+    c->stage_bytes = std::max({sizeof(WorkerMeta) * (size_t)cfg->max_workers, sizeof(int32_t) * (size_t)cfg->queue_capacity,
+                               sizeof(uint64_t) * (size_t)cfg->n_versions});
+    c->ev_slot_read.assign(cfg->n_versions, nullptr);
+    c->ev_slot_written.assign(cfg->n_versions, nullptr);
+    c->slot_read_valid.assign(cfg->n_versions, 0);
+    c->slot_written_valid.assign(cfg->n_versions, 0);
+    hipError_t e = hipStreamCreateWithFlags(&c->server, hipStreamNonBlocking);  // default priority
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_workers, hipEventDisableTiming);
+    for (int i = 0; i < cfg->n_versions && e == hipSuccess; ++i) {
+        e = hipEventCreateWithFlags(&c->ev_slot_read[i], hipEventDisableTiming);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_slot_written[i], hipEventDisableTiming);
+    }
+    if (e == hipSuccess) e = hipHostMalloc((void**)&c->headrb_host, sizeof(unsigned long long) * N_HEADRB, hipHostMallocDefault);
+    for (int i = 0; i < N_HEADRB && e == hipSuccess; ++i) e = hipEventCreateWithFlags(&c->headrb[i].done, hipEventDisableTiming);
     for (int i = 0; i < N_STAGE && e == hipSuccess; ++i) {
         e = hipHostMalloc(&c->stage[i].host, c->stage_bytes, hipHostMallocDefault);
         if (e == hipSuccess) e = hipEventCreateWithFlags(&c->stage[i].done, hipEventDisableTiming);
@@ -255,11 +372,22 @@ ps_status ps_destroy(ps_ctx* c)
 {
     if (!c) return PS_EINVAL;
     (void)hipStreamSynchronize(c->stream);
+    if (c->server) (void)hipStreamSynchronize(c->server);
     c->prof.destroy();
     for (Stage& s : c->stage) {
         if (s.done) (void)hipEventDestroy(s.done);
         if (s.host) (void)hipHostFree(s.host);
     }
+    for (HeadReadback& r : c->headrb)
+        if (r.done) (void)hipEventDestroy(r.done);
+    if (c->headrb_host) (void)hipHostFree(c->headrb_host);
+    for (hipEvent_t ev : c->ev_slot_read)
+        if (ev) (void)hipEventDestroy(ev);
+    for (hipEvent_t ev : c->ev_slot_written)
+        if (ev) (void)hipEventDestroy(ev);
+    if (c->ev_join) (void)hipEventDestroy(c->ev_join);
+    if (c->ev_workers) (void)hipEventDestroy(c->ev_workers);
+    if (c->server) (void)hipStreamDestroy(c->server);
     delete c;
     return PS_OK;
 }
@@ -268,6 +396,8 @@ ps_status ps_sync(ps_ctx* c)
 {
     if (!c) return PS_EINVAL;
     PS_HIP(c, hipStreamSynchronize(c->stream));
+    PS_HIP(c, hipStreamSynchronize(c->server));
+    c->server_dirty = false;
     return PS_OK;
 }
 
@@ -275,6 +405,7 @@ ps_status ps_set_weights(ps_ctx* c, const float* theta_host)
 {
     if (!c || !theta_host) return fail(c, PS_EINVAL, "ps_set_weights: null argument");
     if (!c->pending.empty()) return fail(c, PS_ESTATE, "ps_set_weights: queue not empty");
+    { const ps_status g_ = ordered_guard(c, "ps_set_weights"); if (g_ != PS_OK) return g_; }
     PS_HIP(c, hipMemcpyAsync(c->theta(), theta_host, sizeof(float) * P, hipMemcpyHostToDevice, c->stream));
     for (int s = 0; s < c->cfg.n_versions; ++s) {
         PS_HIP(c, hipMemcpyAsync(c->ring(s), c->theta(), sizeof(float) * PSTRIDE, hipMemcpyDeviceToDevice, c->stream));
@@ -290,6 +421,7 @@ ps_status ps_get_weights(ps_ctx* c, int32_t slot, float* theta_host)
     if (!c || !theta_host) return fail(c, PS_EINVAL, "ps_get_weights: null argument");
     if (slot < -1 || slot >= c->cfg.n_versions) return fail(c, PS_EINVAL, "ps_get_weights: slot out of range");
     const float* src = slot < 0 ? c->theta() : c->ring(slot);
+    PS_HIP(c, hipStreamSynchronize(c->server));
     PS_HIP(c, hipMemcpyAsync(theta_host, src, sizeof(float) * P, hipMemcpyDeviceToHost, c->stream));
     PS_HIP(c, hipStreamSynchronize(c->stream));
     return PS_OK;
@@ -299,6 +431,7 @@ ps_status ps_snapshot_weights(ps_ctx* c, int32_t slot, uint64_t* version_out)
 {
     if (!c) return PS_EINVAL;
     if (slot < 0 || slot >= c->cfg.n_versions) return fail(c, PS_EINVAL, "ps_snapshot_weights: slot out of range");
+    { const ps_status g_ = ordered_guard(c, "ps_snapshot_weights"); if (g_ != PS_OK) return g_; }
     PS_HIP(c, hipMemcpyAsync(c->ring(slot), c->theta(), sizeof(float) * PSTRIDE, hipMemcpyDeviceToDevice, c->stream));
     c->ring_version[slot] = c->version;
     if (version_out) *version_out = c->version;
@@ -320,6 +453,7 @@ ps_status worker_grads_batched(ps_ctx* c, int32_t n, const int32_t* worker_id_ho
         if (version_slot_host[i] < 0 || version_slot_host[i] >= c->cfg.n_versions)
             return fail(c, PS_EINVAL, "worker_grads_batched: version slot out of range");
     if ((size_t)n > c->free_list.size()) return fail(c, PS_EFULL, "worker_grads_batched: gradient queue full");
+    { const ps_status g_ = ordered_guard(c, "worker_grads_batched"); if (g_ != PS_OK) return g_; }
 
     c->last_meta.resize(n);
     for (int i = 0; i < n; ++i) {
@@ -342,6 +476,7 @@ ps_status ps_queue_push_host(ps_ctx* c, const float* grad_host, int32_t worker_i
 {
     if (!c || !grad_host || !queue_index_host) return fail(c, PS_EINVAL, "ps_queue_push_host: null argument");
     if (c->free_list.empty()) return fail(c, PS_EFULL, "ps_queue_push_host: gradient queue full");
+    { const ps_status g_ = ordered_guard(c, "ps_queue_push_host"); if (g_ != PS_OK) return g_; }
     const int32_t q = take_entry(c, worker_id, version, minibatch_id);
     *queue_index_host = q;
     PS_HIP(c, hipMemcpyAsync(c->queue(q), grad_host, sizeof(float) * P, hipMemcpyHostToDevice, c->stream));
@@ -354,6 +489,7 @@ ps_status ps_apply_sync(ps_ctx* c, const int32_t* queue_index_host, int32_t n, f
     if (!c) return PS_EINVAL;
     if (n == 0) return PS_OK;
     if (n < 0 || !queue_index_host) return fail(c, PS_EINVAL, "ps_apply_sync: bad arguments");
+    { const ps_status g_ = ordered_guard(c, "ps_apply_sync"); if (g_ != PS_OK) return g_; }
     std::vector<int32_t> idx(queue_index_host, queue_index_host + n);
     std::vector<char> seen(c->cfg.queue_capacity, 0);
     for (int32_t q : idx) {
@@ -373,6 +509,7 @@ ps_status ps_apply_async(ps_ctx* c, int32_t q, float lr)
     if (!c) return PS_EINVAL;
     if (q < 0 || q >= c->cfg.queue_capacity) return fail(c, PS_EINVAL, "ps_apply_async: queue index out of range");
     if (!c->entries[q].pending) return fail(c, PS_ESTATE, "ps_apply_async: entry not pending");
+    { const ps_status g_ = ordered_guard(c, "ps_apply_async"); if (g_ != PS_OK) return g_; }
     const std::vector<int32_t> idx{q};
     ps_status st = apply_entries(c, idx, lr, PS_DRAIN_SEQ);
     if (st != PS_OK) return st;
@@ -385,6 +522,7 @@ ps_status ps_drain_buffered(ps_ctx* c, int32_t mode, float lr, int32_t* n_applie
 {
     if (!c) return PS_EINVAL;
     if (mode != PS_DRAIN_SUM && mode != PS_DRAIN_SEQ) return fail(c, PS_EINVAL, "ps_drain_buffered: unknown mode");
+    { const ps_status g_ = ordered_guard(c, "ps_drain_buffered"); if (g_ != PS_OK) return g_; }
     const std::vector<int32_t> idx = c->pending;
     if (n_applied_host) *n_applied_host = (int32_t)idx.size();
     if (idx.empty()) return PS_OK;
@@ -401,6 +539,7 @@ ps_status ps_drain_buffered_mitigated(ps_ctx* c, int32_t mode, const ps_drain_po
     if (!c) return PS_EINVAL;
     if (!pol || (mode != PS_DRAIN_SUM && mode != PS_DRAIN_SEQ) || !(pol->lr_backlog_ref >= 0.f) || !(pol->clip_norm >= 0.f))
         return fail(c, PS_EINVAL, "ps_drain_buffered_mitigated: bad mode or policy");
+    { const ps_status g_ = ordered_guard(c, "ps_drain_buffered_mitigated"); if (g_ != PS_OK) return g_; }
     const std::vector<int32_t> idx = c->pending;
     const float K = (float)idx.size();
     const float lr = (pol->lr_backlog_ref > 0.f && K > pol->lr_backlog_ref) ? pol->lr * (pol->lr_backlog_ref / K) : pol->lr;
@@ -419,6 +558,193 @@ ps_status ps_drain_buffered_mitigated(ps_ctx* c, int32_t mode, const ps_drain_po
     }
     release_entries(c, idx);
     c->version += mode == PS_DRAIN_SUM ? 1 : idx.size();
+    return PS_OK;
+}
+
+ps_status worker_grads_append(ps_ctx* c, int32_t n, const int32_t* worker_id_host, const int32_t* version_slot_host,
+                              const uint64_t* minibatch_id_host, const float* x_dev, const int32_t* y_dev, float* loss_dev)
+{
+    if (!c) return PS_EINVAL;
+    if (n == 0) return PS_OK;
+    if (n < 0 || n > c->cfg.max_workers) return fail(c, PS_EINVAL, "worker_grads_append: n outside [0, max_workers]");
+    if (!worker_id_host || !version_slot_host || !minibatch_id_host || !x_dev || !y_dev)
+        return fail(c, PS_EINVAL, "worker_grads_append: null argument");
+    if ((reinterpret_cast<uintptr_t>(x_dev) & 15) || (reinterpret_cast<uintptr_t>(y_dev) & 3))
+        return fail(c, PS_EINVAL, "worker_grads_append: x_dev must be 16-byte and y_dev 4-byte aligned");
+    for (int i = 0; i < n; ++i)
+        if (version_slot_host[i] < 0 || version_slot_host[i] >= c->cfg.n_versions)
+            return fail(c, PS_EINVAL, "worker_grads_append: version slot out of range");
+    ps_status st = store_begin(c, "worker_grads_append");
+    if (st != PS_OK) return st;
+    const uint64_t cap = (uint64_t)c->cfg.queue_capacity;
+    poll_consumed(c);
+    if (c->store_claimed + (uint64_t)n - c->store_confirmed > cap) {
+        PS_HIP(c, hipStreamSynchronize(c->server));  // let enqueued server steps finish, then look again
+        poll_consumed(c);
+        if (c->store_claimed + (uint64_t)n - c->store_confirmed > cap)
+            return fail(c, PS_EFULL, "worker_grads_append: gradient store full");
+    }
+
+    std::vector<int32_t> slots(version_slot_host, version_slot_host + n);
+    std::sort(slots.begin(), slots.end());
+    slots.erase(std::unique(slots.begin(), slots.end()), slots.end());
+    for (int32_t s : slots)
+        if (c->slot_written_valid[s]) PS_HIP(c, hipStreamWaitEvent(c->stream, c->ev_slot_written[s], 0));
+
+    c->last_meta.resize(n);
+    for (int i = 0; i < n; ++i) {
+        const uint64_t mb = minibatch_id_host[i];
+        c->last_meta[i] = WorkerMeta{version_slot_host[i], -1, (uint32_t)mb, (uint32_t)(mb >> 32)};  // row claimed on the device
+    }
+    const StoreBuffers sb = store_buffers(c);
+    WorkerMeta* meta_dev = c->at<WorkerMeta>(c->lay.meta);
+    st = upload(c, meta_dev, c->last_meta.data(), sizeof(WorkerMeta) * n);
+    if (st != PS_OK) return st;
+    st = upload(c, sb.worker_id, worker_id_host, sizeof(int32_t) * n);
+    if (st != PS_OK) return st;
+    PS_HIP(c, launch_store_claim(sb, meta_dev, n, c->stream));
+    c->store_claimed += (uint64_t)n;
+    const WorkerBuffers wb = buffers(c, n, x_dev, y_dev, loss_dev);
+    PS_HIP(c, launch_worker_forward(wb, c->stream, c->prof));
+    PS_HIP(c, launch_worker_backward(wb, c->stream, c->prof));
+    PS_HIP(c, launch_store_publish(sb, meta_dev, n, c->stream));
+    for (int32_t s : slots) {
+        PS_HIP(c, hipEventRecord(c->ev_slot_read[s], c->stream));
+        c->slot_read_valid[s] = 1;
+    }
+    return PS_OK;
+}
+
+ps_status ps_store_consume(ps_ctx* c, int32_t mode, float lr, int32_t max_entries, int32_t wait_for_workers)
+{
+    if (!c) return PS_EINVAL;
+    if ((mode != PS_DRAIN_SUM && mode != PS_DRAIN_SEQ) || max_entries < 0)
+        return fail(c, PS_EINVAL, "ps_store_consume: unknown mode or negative limit");
+    ps_status st = store_begin(c, "ps_store_consume");
+    if (st != PS_OK) return st;
+    const int cap = c->cfg.queue_capacity;
+    const int limit = (max_entries == 0 || max_entries > cap) ? cap : max_entries;
+    if (wait_for_workers) {
+        st = server_waits_workers(c);
+        if (st != PS_OK) return st;
+    }
+    const StoreBuffers sb = store_buffers(c);
+    PS_HIP(c, launch_store_take(sb, limit, c->server));
+    PS_HIP(c, launch_apply(c->theta(), c->at<float>(c->lay.queue), sb.idx, limit, lr, mode, c->server, c->prof, &sb.range->count));
+    PS_HIP(c, launch_store_release(sb, mode, c->server));
+    HeadReadback& r = c->headrb[c->next_headrb];
+    unsigned long long* dst = c->headrb_host + c->next_headrb;
+    c->next_headrb = (c->next_headrb + 1) % N_HEADRB;
+    if (r.in_flight) {
+        PS_HIP(c, hipEventSynchronize(r.done));
+        c->store_confirmed = std::max<uint64_t>(c->store_confirmed, *dst);
+        r.in_flight = false;
+    }
+    PS_HIP(c, hipMemcpyAsync(dst, &sb.state->head, sizeof(unsigned long long), hipMemcpyDeviceToHost, c->server));
+    PS_HIP(c, hipEventRecord(r.done, c->server));
+    r.in_flight = true;
+    c->server_dirty = true;
+    return PS_OK;
+}
+
+ps_status ps_store_publish(ps_ctx* c, int32_t slot)
+{
+    if (!c) return PS_EINVAL;
+    if (slot < 0 || slot >= c->cfg.n_versions) return fail(c, PS_EINVAL, "ps_store_publish: slot out of range");
+    ps_status st = store_begin(c, "ps_store_publish");
+    if (st != PS_OK) return st;
+    if (c->slot_read_valid[slot]) PS_HIP(c, hipStreamWaitEvent(c->server, c->ev_slot_read[slot], 0));
+    PS_HIP(c, hipMemcpyAsync(c->ring(slot), c->theta(), sizeof(float) * PSTRIDE, hipMemcpyDeviceToDevice, c->server));
+    PS_HIP(c, launch_store_stamp_version(store_buffers(c), slot, c->server));
+    PS_HIP(c, hipEventRecord(c->ev_slot_written[slot], c->server));
+    c->slot_written_valid[slot] = 1;
+    c->server_dirty = true;
+    return PS_OK;
+}
+
+namespace {
+
+// Both streams idle; device counters, stamps and snapshot versions on the host.
+ps_status store_read(ps_ctx* c, StoreState* state, std::vector<unsigned long long>* stamps)
+{
+    PS_HIP(c, hipStreamSynchronize(c->stream));
+    PS_HIP(c, hipStreamSynchronize(c->server));
+    c->server_dirty = false;
+    const StoreBuffers sb = store_buffers(c);
+    PS_HIP(c, hipMemcpy(state, sb.state, sizeof(StoreState), hipMemcpyDeviceToHost));
+    if (stamps) {
+        stamps->resize(sb.cap);
+        PS_HIP(c, hipMemcpy(stamps->data(), sb.stamp, sizeof(unsigned long long) * sb.cap, hipMemcpyDeviceToHost));
+    }
+    for (HeadReadback& r : c->headrb) r.in_flight = false;  // all finished; superseded by the value just read
+    if (c->store_synced) {  // the device holds the authoritative counters
+        c->store_confirmed = state->head;
+        c->version = state->version;
+        std::vector<unsigned long long> rv(c->cfg.n_versions);
+        PS_HIP(c, hipMemcpy(rv.data(), sb.ring_version, sizeof(unsigned long long) * rv.size(), hipMemcpyDeviceToHost));
+        for (size_t i = 0; i < rv.size(); ++i) c->ring_version[i] = rv[i];
+    }
+    return PS_OK;
+}
+
+uint64_t published_prefix(const ps_ctx* c, const StoreState& s, const std::vector<unsigned long long>& stamps)
+{
+    uint64_t p = s.head;
+    while (p < s.tail && stamps[p % (uint64_t)c->cfg.queue_capacity] == p + 1) ++p;
+    return p;
+}
+
+}  // namespace
+
+ps_status ps_store_state(ps_ctx* c, ps_store_counters* out)
+{
+    if (!c || !out) return fail(c, PS_EINVAL, "ps_store_state: null argument");
+    StoreState s{};
+    std::vector<unsigned long long> stamps;
+    ps_status st = store_read(c, &s, &stamps);
+    if (st != PS_OK) return st;
+    out->claimed = s.tail;
+    out->published = published_prefix(c, s, stamps);
+    out->consumed = s.head;
+    out->version = c->store_synced ? s.version : c->version;
+    out->steps = s.log_n;
+    return PS_OK;
+}
+
+ps_status ps_store_steps(ps_ctx* c, int32_t capacity, int32_t* n_host, ps_store_step* steps_host)
+{
+    if (!c || !n_host || capacity < 0 || (capacity > 0 && !steps_host)) return fail(c, PS_EINVAL, "ps_store_steps: bad arguments");
+    StoreState s{};
+    ps_status st = store_read(c, &s, nullptr);
+    if (st != PS_OK) return st;
+    const uint64_t m = std::min<uint64_t>({s.log_n, (uint64_t)STORE_LOG_CAP, (uint64_t)capacity});
+    std::vector<StoreLogRec> log(STORE_LOG_CAP);
+    PS_HIP(c, hipMemcpy(log.data(), store_buffers(c).log, sizeof(StoreLogRec) * STORE_LOG_CAP, hipMemcpyDeviceToHost));
+    for (uint64_t i = 0; i < m; ++i) {
+        const StoreLogRec& r = log[(s.log_n - m + i) % STORE_LOG_CAP];
+        steps_host[i] = ps_store_step{r.first, r.count, r.mode, r.version_after};
+    }
+    *n_host = (int32_t)m;
+    return PS_OK;
+}
+
+ps_status ps_store_entry(ps_ctx* c, uint64_t position, float* grad_host, int32_t* worker_host, uint64_t* version_host,
+                         uint64_t* minibatch_host)
+{
+    if (!c) return PS_EINVAL;
+    StoreState s{};
+    std::vector<unsigned long long> stamps;
+    ps_status st = store_read(c, &s, &stamps);
+    if (st != PS_OK) return st;
+    if (position < s.head || position >= published_prefix(c, s, stamps))
+        return fail(c, PS_ESTATE, "ps_store_entry: position already consumed or not yet published");
+    const int q = (int)(position % (uint64_t)c->cfg.queue_capacity);
+    StoreEntryMeta e{};
+    PS_HIP(c, hipMemcpy(&e, store_buffers(c).entry + q, sizeof(e), hipMemcpyDeviceToHost));
+    if (grad_host) PS_HIP(c, hipMemcpy(grad_host, c->queue(q), sizeof(float) * P, hipMemcpyDeviceToHost));
+    if (worker_host) *worker_host = e.worker;
+    if (version_host) *version_host = e.version;
+    if (minibatch_host) *minibatch_host = e.mb;
     return PS_OK;
 }
 
@@ -454,6 +780,7 @@ ps_status ps_restore_weights(ps_ctx* c, int32_t slot, int32_t* n_dropped_host)
 {
     if (!c) return PS_EINVAL;
     if (slot < 0 || slot >= c->cfg.n_versions) return fail(c, PS_EINVAL, "ps_restore_weights: slot out of range");
+    { const ps_status g_ = ordered_guard(c, "ps_restore_weights"); if (g_ != PS_OK) return g_; }
     PS_HIP(c, hipMemcpyAsync(c->theta(), c->ring(slot), sizeof(float) * PSTRIDE, hipMemcpyDeviceToDevice, c->stream));
     if (n_dropped_host) *n_dropped_host = (int32_t)c->pending.size();
     const std::vector<int32_t> idx = c->pending;
@@ -473,6 +800,7 @@ ps_status ps_evaluate(ps_ctx* c, int32_t slot, int32_t n_images, const float* x_
     if (!x_dev || !y_dev || (reinterpret_cast<uintptr_t>(x_dev) & 15) || (reinterpret_cast<uintptr_t>(y_dev) & 3))
         return fail(c, PS_EINVAL, "ps_evaluate: null or misaligned input");
     const int n = n_images / B;
+    PS_HIP(c, hipStreamSynchronize(c->server));
     std::vector<WorkerMeta> meta(n, WorkerMeta{slot, 0, 0, 0});
     c->last_meta.clear();  // the activations of the last worker call are overwritten
     ps_status st = upload(c, c->at<WorkerMeta>(c->lay.meta), meta.data(), sizeof(WorkerMeta) * n);
@@ -535,6 +863,7 @@ ps_status ps_debug_last_batch(ps_ctx* c, int32_t i, uint8_t* pool1_host, uint8_t
 ps_status ps_profile_enable(ps_ctx* c, int32_t enable)
 {
     if (!c) return PS_EINVAL;
+    PS_HIP(c, hipStreamSynchronize(c->server));
     PS_HIP(c, c->prof.collect(c->stream));
     c->prof.reset();
     c->prof.enabled = enable != 0;
@@ -544,6 +873,7 @@ ps_status ps_profile_enable(ps_ctx* c, int32_t enable)
 ps_status ps_profile_read(ps_ctx* c, int32_t kernel_id, double* total_ms_host, int64_t* launches_host)
 {
     if (!c || kernel_id < 0 || kernel_id >= K_COUNT) return fail(c, PS_EINVAL, "ps_profile_read: no such kernel");
+    PS_HIP(c, hipStreamSynchronize(c->server));
     PS_HIP(c, c->prof.collect(c->stream));
     if (total_ms_host) *total_ms_host = c->prof.total_ms[kernel_id];
     if (launches_host) *launches_host = c->prof.launches[kernel_id];

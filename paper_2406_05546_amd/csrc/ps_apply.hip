@@ -23,10 +23,12 @@ __device__ __forceinline__ float4 ld_stream(const float4* p)
 template <int MODE, bool SCALED>
 __global__ __launch_bounds__(256) void apply_kernel(float4* __restrict__ theta, const float4* __restrict__ queue,
                                                      const int32_t* __restrict__ idx, int K, float lr,
-                                                     const float* __restrict__ scale)
+                                                     const float* __restrict__ scale,
+                                                     const uint32_t* __restrict__ K_dev)
 {
     const int i = blockIdx.x * 256 + threadIdx.x;
     if (i >= ROW4) return;
+    if (K_dev) K = (int)*K_dev;  // the consumer of the lock-free store learns the count on the device
     float4 t = theta[i];
     float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
     const float4* col = queue + i;
@@ -110,17 +112,17 @@ __global__ __launch_bounds__(256) void clip_scale_kernel(const float* __restrict
 }  // namespace
 
 hipError_t launch_apply(float* theta, const float* queue, const int32_t* idx_dev, int K, float lr, int mode,
-                        hipStream_t s, Profiler& prof)
+                        hipStream_t s, Profiler& prof, const uint32_t* K_dev)
 {
     if (K <= 0) return hipSuccess;
     dim3 grid((ROW4 + 255) / 256), block(256);
     prof.begin(mode == 0 ? K_APPLY_SUM : K_APPLY_SEQ, s);
     if (mode == 0)
         hipLaunchKernelGGL((apply_kernel<0, false>), grid, block, 0, s, (float4*)theta, (const float4*)queue, idx_dev, K, lr,
-                           (const float*)nullptr);
+                           (const float*)nullptr, K_dev);
     else
         hipLaunchKernelGGL((apply_kernel<1, false>), grid, block, 0, s, (float4*)theta, (const float4*)queue, idx_dev, K, lr,
-                           (const float*)nullptr);
+                           (const float*)nullptr, K_dev);
     prof.end(s);
     return hipGetLastError();
 }
@@ -137,10 +139,10 @@ hipError_t launch_apply_clipped(float* theta, const float* queue, const int32_t*
     prof.begin(mode == 0 ? K_APPLY_SUM_CLIP : K_APPLY_SEQ_CLIP, s);
     if (mode == 0)
         hipLaunchKernelGGL((apply_kernel<0, true>), grid, block, 0, s, (float4*)theta, (const float4*)queue, idx_dev, K, lr,
-                           (const float*)scale_dev);
+                           (const float*)scale_dev, (const uint32_t*)nullptr);
     else
         hipLaunchKernelGGL((apply_kernel<1, true>), grid, block, 0, s, (float4*)theta, (const float4*)queue, idx_dev, K, lr,
-                           (const float*)scale_dev);
+                           (const float*)scale_dev, (const uint32_t*)nullptr);
     prof.end(s);
     return hipGetLastError();
 }

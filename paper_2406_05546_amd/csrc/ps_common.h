@@ -130,12 +130,56 @@ hipError_t launch_keep_mask(uint8_t* keep_dev, int B, uint32_t mb_lo, uint32_t m
                             uint32_t seed_hi, uint32_t threshold, hipStream_t s);
 
 // theta -= lr * (sum of the K listed queue rows) [mode 0] or K successive updates [mode 1].
+// With K_dev the number of rows is read from device memory by the kernel (at most K_max).
 hipError_t launch_apply(float* theta, const float* queue, const int32_t* idx_dev, int K, float lr, int mode,
-                        hipStream_t s, Profiler& prof);
+                        hipStream_t s, Profiler& prof, const uint32_t* K_dev = nullptr);
 
 // Same with every gradient first scaled by min(1, clip / ||g||_2): a norm pass, then the apply pass.
 hipError_t launch_apply_clipped(float* theta, const float* queue, const int32_t* idx_dev, int K, float lr, int mode,
                                 float clip, float* partial_dev, float* scale_dev, hipStream_t s, Profiler& prof);
 int norm_slices();
+
+// Lock-free gradient store (Section 3.3, last paragraph: a gradient is written once by its worker,
+// read once and then deleted by the server, so the store needs no lock).  Positions count appended
+// gradients from 0 and never wrap; position p lives in queue row p % capacity.
+struct StoreState {
+    unsigned long long tail;     // positions claimed by workers
+    unsigned long long head;     // positions consumed (applied and deleted) by the server
+    unsigned long long version;  // weight updates applied
+    unsigned long long log_n;    // consumer steps recorded
+};
+struct StoreEntryMeta {
+    unsigned long long pos, version, mb;  // position, version of the snapshot used, minibatch id
+    int32_t worker, pad;
+};
+struct StoreLogRec {  // one consumer step that applied at least one gradient
+    unsigned long long first;
+    uint32_t count, mode;
+    unsigned long long version_after;
+};
+struct StoreRange {  // what the consumer step in flight has taken
+    unsigned long long first;
+    uint32_t count, pad;
+};
+constexpr int STORE_LOG_CAP = 1024;
+
+struct StoreBuffers {
+    StoreState* state;
+    unsigned long long* stamp;         // [cap] position + 1 once the row is completely written
+    StoreEntryMeta* entry;             // [cap]
+    unsigned long long* ring_version;  // [V]
+    StoreLogRec* log;                  // [STORE_LOG_CAP], a ring
+    StoreRange* range;
+    int32_t* idx;                      // [cap] rows taken by the consumer step in flight
+    int32_t* worker_id;                // [max_workers] of the append in flight
+    int cap;
+};
+
+hipError_t launch_store_reset(const StoreBuffers& sb, unsigned long long version, hipStream_t s);
+hipError_t launch_store_claim(const StoreBuffers& sb, WorkerMeta* meta, int n, hipStream_t s);
+hipError_t launch_store_publish(const StoreBuffers& sb, const WorkerMeta* meta, int n, hipStream_t s);
+hipError_t launch_store_take(const StoreBuffers& sb, int max_entries, hipStream_t s);
+hipError_t launch_store_release(const StoreBuffers& sb, int mode, hipStream_t s);
+hipError_t launch_store_stamp_version(const StoreBuffers& sb, int slot, hipStream_t s);
 
 }  // namespace ps

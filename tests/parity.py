@@ -85,14 +85,15 @@ def decisions(dbg: dict, rec, keep: np.ndarray, p: float, what: str, tie_tol: fl
 
 
 def check_worker(ps, ctx, i: int, entry: int, theta: np.ndarray, x: np.ndarray, y: np.ndarray, mb_id: int,
-                 drop_seed: int, p: float, what: str, tie_tol: float = TIE_TOL) -> dict:
+                 drop_seed: int, p: float, what: str, tie_tol: float = TIE_TOL, grad: np.ndarray = None) -> dict:
     """Full parity of worker i of the last batched call: masks, decisions, gradient.
-    theta is the oracle's snapshot for that worker (fp64)."""
+    theta is the oracle's snapshot for that worker (fp64).  The gradient is read from queue entry
+    `entry`, unless the caller read it already (`grad`, e.g. from the lock-free store)."""
     B = x.shape[0]
     keep = orc.dropout_keep(drop_seed, mb_id, B, 512, p)
     g_ref, l_ref, rec = orc.worker_grad(orc.Dims(), theta, x, y, keep, p, records=True)
     forced, n_free = decisions(ps.ps_debug_last_batch(ctx, i), rec, keep, p, what, tie_tol)
     if len(forced):
         g_ref, l_ref = orc.worker_grad(orc.Dims(), theta, x, y, keep, p, forced=forced)
-    errs = assert_close(ps.ps_get_grad(ctx, entry), g_ref, GRAD_TOL, what)
+    errs = assert_close(ps.ps_get_grad(ctx, entry) if grad is None else grad, g_ref, GRAD_TOL, what)
     return {"worst": max(errs.values()), "near_ties": n_free, "forced": len(forced), "loss": l_ref, "grad": g_ref}

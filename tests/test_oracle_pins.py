@@ -476,3 +476,30 @@ def test_restore_continues_from_the_checkpointed_state():
     assert seen == [0, 2]                                   # the in-flight kill loses that step's two gradients
     # updates 1,2 -> checkpoint; update 3, kill -> back to 2; update -> 3, checkpoint; in-flight kill -> 3
     assert o.server.version == 3
+
+
+def test_store_consume_is_a_prefix_in_arrival_order_read_once_then_deleted():
+    """Section 3.3, last paragraph: write once, read once, delete.  Closed forms on hand-made
+    gradients g_i = (i + 1) * e_i: a SUM step over the first k moves exactly coordinates 0..k-1 by
+    lr * (i + 1) in one version; SEQ steps split anywhere give what one step gives; nothing is
+    applied twice and the rest stays pending in order."""
+    n, lr = 6, 0.5
+    def server():
+        s = orc.OracleServer(TINY, 7, 0.25, 1, np.zeros(n))
+        for i in range(n):
+            g = np.zeros(n)
+            g[i] = i + 1.0
+            s.pending.append(orc.QueueEntry(s.next_seq, i, 0, 100 + i, g, 0.0))
+            s.next_seq += 1
+        return s
+    s = server()
+    assert s.consume(orc.DRAIN_SUM, lr, 4) == 4
+    assert np.array_equal(s.theta, [-0.5, -1.0, -1.5, -2.0, 0, 0]) and s.version == 1
+    assert [e.seq for e in s.pending] == [4, 5]
+    assert s.consume(orc.DRAIN_SEQ, lr, 10) == 2 and s.version == 3 and not s.pending
+    assert np.array_equal(s.theta, -lr * np.arange(1.0, n + 1))
+    assert s.consume(orc.DRAIN_SEQ, lr, 3) == 0 and s.version == 3          # empty store: nothing happens
+    a, b = server(), server()
+    a.consume(orc.DRAIN_SEQ, lr, 2), a.consume(orc.DRAIN_SEQ, lr, 1), a.consume(orc.DRAIN_SEQ, lr, 3)
+    b.consume(orc.DRAIN_SEQ, lr, n)
+    assert np.array_equal(a.theta, b.theta) and a.version == b.version == n
