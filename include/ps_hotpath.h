@@ -22,6 +22,8 @@
  *     enqueued work; pointers named *_host are HOST pointers owned by the caller.
  *   - All GPU work is enqueued on the HIP stream given to ps_init and is
  *     asynchronous; the ps_get_*, ps_debug_* and ps_sync calls wait for it.
+ *     Only the server side of the lock-free store (below) runs on a second
+ *     stream, which the context creates at default priority.
  *   - The library allocates no device memory: the caller hands ps_init one
  *     device workspace of ps_workspace_bytes() bytes, which the context carves
  *     into weights, snapshot ring, gradient queue and activations, and which
