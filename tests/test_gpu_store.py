@@ -259,3 +259,38 @@ def test_store_full_size_overlapped_rounds(ps):
         assert np.array_equal(ps.ps_get_weights(ctx, 1), ordered)
     finally:
         ps.ps_destroy(ctx)
+
+
+def test_store_many_small_steps_wrap_the_step_log_and_the_readback_ring(ps):
+    """1100 one-gradient appends, each consumed by its own server step, over a 3-row queue: the
+    device keeps the last 1024 steps, positions wrap the queue 366 times, and the host's view of the
+    consumed count has to keep up without ever reporting a full store.  The weights must equal, bit
+    for bit, those of the ordered path applying the same 1100 gradients one by one."""
+    B, STEPS, lr = 2, 1100, 0.01
+    theta0 = synth.he_uniform_theta(12)
+    mbs = [synth.minibatch_id(0, k) for k in range(8)]
+    x, y = synth.minibatches(DATA_SEED, mbs, B)
+    xd, yd = _dev(x, y)
+    ctx = ps.ps_init(ps.make_config(1, B, 1, 3, DROP_SEED, P_DROP))
+    try:
+        ps.ps_set_weights(ctx, theta0)
+        for k in range(STEPS):
+            i = k % 8
+            (q,) = ps.worker_grads_batched(ctx, [0], [0], [mbs[i]], xd[i:i + 1], yd[i:i + 1])
+            ps.ps_apply_async(ctx, q, lr)
+        ordered = ps.ps_get_weights(ctx)
+        assert ps.ps_version(ctx) == STEPS
+        ps.ps_set_weights(ctx, theta0)
+        say("store small steps: 1100 appends")
+        for k in range(STEPS):
+            i = k % 8
+            ps.worker_grads_append(ctx, [0], [0], [mbs[i]], xd[i:i + 1], yd[i:i + 1])
+            ps.ps_store_consume(ctx, ps.DRAIN_SEQ, lr, 0, True)
+        st = ps.ps_store_state(ctx)
+        assert st == {"claimed": STEPS, "published": STEPS, "consumed": STEPS, "version": STEPS, "steps": STEPS}
+        steps = ps.ps_store_steps(ctx, 2000)
+        assert steps == [(k, 1, 1, k + 1) for k in range(STEPS - 1024, STEPS)]
+        assert ps.ps_store_steps(ctx, 5) == [(k, 1, 1, k + 1) for k in range(STEPS - 5, STEPS)]
+        assert np.array_equal(ps.ps_get_weights(ctx), ordered)
+    finally:
+        ps.ps_destroy(ctx)
