@@ -68,7 +68,11 @@ struct Fc1DwEpi {
 
 }  // namespace
 
-// All three use 128 x 128 block tiles (four wavefronts of 64 x 64), K stepped 16 at a time.
+// All three use 128 x 128 block tiles (four wavefronts of 64 x 64), K stepped 16 at a time.  The 1568
+// features are 12 such tiles plus 32: that edge gets its own launch with 32-wide tiles (four
+// wavefronts of 32 x 32 side by side) instead of a thirteenth wide tile that would be three quarters
+// empty.
+constexpr int FEAT_WIDE = P2_SIZE / 128 * 128;  // 1536
 
 // forward: rows = 512 units (W3, k-contiguous), columns = the worker's samples (pool2, k-contiguous)
 void launch_fc1_fwd(const WorkerBuffers& wb, hipStream_t s)
@@ -80,14 +84,18 @@ void launch_fc1_fwd(const WorkerBuffers& wb, hipStream_t s)
 // contraction over the worker's samples
 void launch_fc1_dw(const WorkerBuffers& wb, hipStream_t s)
 {
-    gemm_launch<false, false, 2, 2, 2, 2, 16, 1>(FC1, P2_SIZE, wb.B, FC1, P2_SIZE, wb.n, Fc1DwEpi{wb}, s);
+    const Fc1DwEpi epi{wb};
+    gemm_launch_range<false, false, 2, 2, 2, 2, 16, 1>(FC1, P2_SIZE, wb.B, FC1, P2_SIZE, wb.n, 0, FC1, 0, FEAT_WIDE, epi, s);
+    gemm_launch_range<false, false, 1, 1, 4, 1, 16, 1>(FC1, P2_SIZE, wb.B, FC1, P2_SIZE, wb.n, 0, FC1, FEAT_WIDE, P2_SIZE, epi, s);
 }
 
 // input gradient: rows = 1568 features (W3, row-contiguous), columns = samples (d3, k-contiguous),
 // contraction over the 512 units
 void launch_fc1_dx(const WorkerBuffers& wb, hipStream_t s)
 {
-    gemm_launch<false, true, 2, 2, 2, 2, 16, 1>(P2_SIZE, wb.B, FC1, P2_SIZE, FC1, wb.n, Fc1DxEpi{wb}, s);
+    const Fc1DxEpi epi{wb};
+    gemm_launch_range<false, true, 2, 2, 2, 2, 16, 1>(P2_SIZE, wb.B, FC1, P2_SIZE, FC1, wb.n, 0, FEAT_WIDE, 0, wb.B, epi, s);
+    gemm_launch_range<false, true, 1, 1, 1, 4, 16, 1>(P2_SIZE, wb.B, FC1, P2_SIZE, FC1, wb.n, FEAT_WIDE, P2_SIZE, 0, wb.B, epi, s);
 }
 
 }  // namespace ps

@@ -34,6 +34,7 @@ struct GemmShape {
     int M, N, K;     // M % 4 == 0; K % 4 == 0 when an operand is KC
     int lda, ldb;
     int gx, gy, gz;  // tiles along M, along N, batch size
+    int m_base, n_base;  // origin of the tile grid inside C (a launch may cover only part of C)
 };
 
 // Operand tiles are read with unconditional loads from addresses that are clamped into the operand,
@@ -125,7 +126,7 @@ __global__ __launch_bounds__(256, MINW) void gemm_f32_mfma(GemmShape sh, Epi epi
     const int total = sh.gx * sh.gy * sh.gz, per_xcd = (total + GEMM_XCDS - 1) / GEMM_XCDS;
     const int v = (blockIdx.x % GEMM_XCDS) * per_xcd + blockIdx.x / GEMM_XCDS;
     if (v >= total) return;
-    const int m0 = (v % sh.gx) * BM, n0 = (v / sh.gx % sh.gy) * BN, z = v / (sh.gx * sh.gy);
+    const int m0 = sh.m_base + (v % sh.gx) * BM, n0 = sh.n_base + (v / sh.gx % sh.gy) * BN, z = v / (sh.gx * sh.gy);
     const float* __restrict__ A = epi.a_ptr(z);
     const float* __restrict__ B = epi.b_ptr(z);
 
@@ -205,12 +206,17 @@ __global__ __launch_bounds__(256, MINW) void gemm_f32_mfma(GemmShape sh, Epi epi
         }
 }
 
-// Launches one GEMM per batch index over a 1-D grid padded to a multiple of the XCD count.
+// Launches, per batch index, the tiles that cover rows [m_begin, m_end) and columns [n_begin, n_end)
+// of C (begins must be multiples of the instance's block tile unless zero) over a 1-D grid padded to
+// a multiple of the XCD count.  Covering C with a wide-tile launch plus a narrow-tile launch for the
+// ragged edge avoids running a mostly empty wide tile.
 template <bool A_KC, bool B_KC, int TM, int TN, int WM, int WN, int KS, int MINW, class Epi>
-void gemm_launch(int M, int N, int K, int lda, int ldb, int batch, const Epi& epi, hipStream_t s)
+void gemm_launch_range(int M, int N, int K, int lda, int ldb, int batch, int m_begin, int m_end, int n_begin, int n_end,
+                       const Epi& epi, hipStream_t s)
 {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
-    GemmShape sh{M, N, K, lda, ldb, (M + BM - 1) / BM, (N + BN - 1) / BN, batch};
+    if (m_end <= m_begin || n_end <= n_begin || batch <= 0) return;
+    GemmShape sh{M, N, K, lda, ldb, (m_end - m_begin + BM - 1) / BM, (n_end - n_begin + BN - 1) / BN, batch, m_begin, n_begin};
     const int total = sh.gx * sh.gy * sh.gz;
     const int grid = (total + GEMM_XCDS - 1) / GEMM_XCDS * GEMM_XCDS;
     if (K % KS == 0)
@@ -219,6 +225,12 @@ void gemm_launch(int M, int N, int K, int lda, int ldb, int batch, const Epi& ep
     else
         hipLaunchKernelGGL((gemm_f32_mfma<A_KC, B_KC, TM, TN, WM, WN, KS, true, MINW, Epi>), dim3(grid), dim3(256), 0, s,
                            sh, epi);
+}
+
+template <bool A_KC, bool B_KC, int TM, int TN, int WM, int WN, int KS, int MINW, class Epi>
+void gemm_launch(int M, int N, int K, int lda, int ldb, int batch, const Epi& epi, hipStream_t s)
+{
+    gemm_launch_range<A_KC, B_KC, TM, TN, WM, WN, KS, MINW>(M, N, K, lda, ldb, batch, 0, M, 0, N, epi, s);
 }
 
 }  // namespace ps
