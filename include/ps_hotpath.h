@@ -183,10 +183,12 @@ PS_API ps_status ps_evaluate(ps_ctx* ctx, int32_t slot, int32_t n_images, const 
  * measured in the paper takes a lock instead, and the Future Work section lists a better mechanism.
  * Here the store's state lives in device memory.  Workers (the stream given to ps_init) and the
  * server (a second stream the context creates, same priority) run concurrently and meet only there:
- * a batch of workers claims consecutive positions with one atomic add, writes its gradient rows and
- * then stamps them as complete; a server step takes the longest prefix of complete rows not yet
+ * a batch of workers writes its gradient rows, then claims consecutive positions with one atomic add
+ * and stamps the rows as complete; a server step takes the longest prefix of complete rows not yet
  * consumed, applies it in position order and deletes it by advancing the consumed count.  Positions
- * count appended gradients from 0 and never wrap; position p uses queue row p % queue_capacity.
+ * count appended gradients from 0 and never wrap; position p uses queue row p % queue_capacity (the
+ * host, which enqueues all appends on the one worker stream, knows the rows in advance; the device
+ * checks that the claim lands on them).
  *
  * While the store holds gradients that the host has not yet seen consumed (ps_store_state tells),
  * the calls above that touch the queue or the server's weights return PS_ESTATE; the store calls in
@@ -208,9 +210,9 @@ typedef struct {
     uint64_t version_after; /* version once it was applied      */
 } ps_store_step;
 
-/* Worker step as worker_grads_batched, but the queue rows are claimed on the device and nothing
- * about them comes back to the host: the n gradients take positions claimed .. claimed + n - 1 in
- * array order.  Waits (on the device, not the host) for the last ps_store_publish into each ring slot
+/* Worker step as worker_grads_batched, but into the store: the n gradients take positions
+ * claimed .. claimed + n - 1 in array order, claimed and stamped on the device when their rows are
+ * complete; no queue index comes back.  Waits (on the device, not the host) for the last ps_store_publish into each ring slot
  * it reads.  PS_EFULL if claimed + n - consumed could exceed queue_capacity by what the host has seen
  * so far (it looks again, waiting for the server stream, before giving up); PS_ESTATE if the ordered
  * queue above is not empty. */

@@ -594,7 +594,8 @@ ps_status worker_grads_append(ps_ctx* c, int32_t n, const int32_t* worker_id_hos
     c->last_meta.resize(n);
     for (int i = 0; i < n; ++i) {
         const uint64_t mb = minibatch_id_host[i];
-        c->last_meta[i] = WorkerMeta{version_slot_host[i], -1, (uint32_t)mb, (uint32_t)(mb >> 32)};  // row claimed on the device
+        const int32_t row = (int32_t)((c->store_claimed + (uint64_t)i) % cap);  // the position this append will claim
+        c->last_meta[i] = WorkerMeta{version_slot_host[i], row, (uint32_t)mb, (uint32_t)(mb >> 32)};
     }
     const StoreBuffers sb = store_buffers(c);
     WorkerMeta* meta_dev = c->at<WorkerMeta>(c->lay.meta);
@@ -602,7 +603,6 @@ ps_status worker_grads_append(ps_ctx* c, int32_t n, const int32_t* worker_id_hos
     if (st != PS_OK) return st;
     st = upload(c, sb.worker_id, worker_id_host, sizeof(int32_t) * n);
     if (st != PS_OK) return st;
-    PS_HIP(c, launch_store_claim(sb, meta_dev, n, c->stream));
     c->store_claimed += (uint64_t)n;
     const WorkerBuffers wb = buffers(c, n, x_dev, y_dev, loss_dev);
     PS_HIP(c, launch_worker_forward(wb, c->stream, c->prof));
@@ -676,6 +676,7 @@ ps_status store_read(ps_ctx* c, StoreState* state, std::vector<unsigned long lon
         stamps->resize(sb.cap);
         PS_HIP(c, hipMemcpy(stamps->data(), sb.stamp, sizeof(unsigned long long) * sb.cap, hipMemcpyDeviceToHost));
     }
+    if (state->fault) return fail(c, PS_EDEVICE, "lock-free store: an append claimed positions other than the rows it had written");
     for (HeadReadback& r : c->headrb) r.in_flight = false;  // all finished; superseded by the value just read
     if (c->store_synced) {  // the device holds the authoritative counters
         c->store_confirmed = state->head;

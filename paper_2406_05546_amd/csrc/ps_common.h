@@ -147,6 +147,7 @@ struct StoreState {
     unsigned long long head;     // positions consumed (applied and deleted) by the server
     unsigned long long version;  // weight updates applied
     unsigned long long log_n;    // consumer steps recorded
+    unsigned long long fault;    // set if an append did not land on the rows the host predicted
 };
 struct StoreEntryMeta {
     unsigned long long pos, version, mb;  // position, version of the snapshot used, minibatch id
@@ -176,7 +177,6 @@ struct StoreBuffers {
 };
 
 hipError_t launch_store_reset(const StoreBuffers& sb, unsigned long long version, hipStream_t s);
-hipError_t launch_store_claim(const StoreBuffers& sb, WorkerMeta* meta, int n, hipStream_t s);
 hipError_t launch_store_publish(const StoreBuffers& sb, const WorkerMeta* meta, int n, hipStream_t s);
 hipError_t launch_store_take(const StoreBuffers& sb, int max_entries, hipStream_t s);
 hipError_t launch_store_release(const StoreBuffers& sb, int mode, hipStream_t s);

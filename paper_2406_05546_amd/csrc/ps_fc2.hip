@@ -12,6 +12,35 @@ namespace ps {
 
 namespace {
 
+// Sum over the 64 lanes of a wavefront, the same value returned in every lane.  Data-parallel
+// primitives (lane permutes inside the vector ALU) instead of shuffles through the LDS crossbar:
+// butterflies inside quads and rows of 16, then the row sums are passed up rows 0 -> 1, {0,1} -> {2,3},
+// which leaves the total in lane 63.
+__device__ __forceinline__ float wave_sum(float v)
+{
+    auto dpp_add = [](float x, int ctrl, int row_mask) {
+        const int moved = 0;  // rows outside the mask add nothing
+        int r;
+        switch (ctrl) {
+            case 0: r = __builtin_amdgcn_update_dpp(moved, __float_as_int(x), 0xB1, 0xF, 0xF, false); break;   // quad_perm [1,0,3,2]
+            case 1: r = __builtin_amdgcn_update_dpp(moved, __float_as_int(x), 0x4E, 0xF, 0xF, false); break;   // quad_perm [2,3,0,1]
+            case 2: r = __builtin_amdgcn_update_dpp(moved, __float_as_int(x), 0x141, 0xF, 0xF, false); break;  // row_half_mirror
+            case 3: r = __builtin_amdgcn_update_dpp(moved, __float_as_int(x), 0x140, 0xF, 0xF, false); break;  // row_mirror
+            case 4: r = __builtin_amdgcn_update_dpp(moved, __float_as_int(x), 0x142, 0xA, 0xF, false); break;  // row_bcast:15 into rows 1, 3
+            default: r = __builtin_amdgcn_update_dpp(moved, __float_as_int(x), 0x143, 0xC, 0xF, false); break; // row_bcast:31 into rows 2, 3
+        }
+        (void)row_mask;
+        return x + __int_as_float(r);
+    };
+    v = dpp_add(v, 0, 0xF);
+    v = dpp_add(v, 1, 0xF);
+    v = dpp_add(v, 2, 0xF);
+    v = dpp_add(v, 3, 0xF);
+    v = dpp_add(v, 4, 0xA);
+    v = dpp_add(v, 5, 0xC);
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+
 __global__ __launch_bounds__(256) void fc2_kernel(WorkerBuffers wb)
 {
     const int lane = threadIdx.x & 63, w = blockIdx.x, B = wb.B;
@@ -53,9 +82,7 @@ __global__ __launch_bounds__(256) void fc2_kernel(WorkerBuffers wb)
             float part = 0.f;
 #pragma unroll
             for (int j = 0; j < 8; ++j) part = fmaf(hv[j], w4[c][j], part);
-#pragma unroll
-            for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off, 64);
-            z[c] = part + b4[c];
+            z[c] = wave_sum(part) + b4[c];
         }
         const int label = wb.y[g];
         float zmax = z[0];
@@ -63,14 +90,17 @@ __global__ __launch_bounds__(256) void fc2_kernel(WorkerBuffers wb)
 #pragma unroll
         for (int c = 1; c < NCLS; ++c)
             if (z[c] > zmax) { zmax = z[c]; pred = c; }
-        float se = 0.f;
+        float e[NCLS], se = 0.f;
 #pragma unroll
-        for (int c = 0; c < NCLS; ++c) se += expf(z[c] - zmax);
-        const float lse = zmax + logf(se);
+        for (int c = 0; c < NCLS; ++c) {
+            e[c] = expf(z[c] - zmax);
+            se += e[c];
+        }
+        const float lse = zmax + logf(se), inv_se = 1.f / se;
         float d4[NCLS], zy = 0.f;
 #pragma unroll
         for (int c = 0; c < NCLS; ++c) {
-            d4[c] = (expf(z[c] - lse) - (c == label ? 1.f : 0.f)) * inv_b;
+            d4[c] = (e[c] * inv_se - (c == label ? 1.f : 0.f)) * inv_b;
             if (c == label) zy = z[c];
             accb4[c] += d4[c];
         }

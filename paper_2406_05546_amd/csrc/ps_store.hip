@@ -2,8 +2,11 @@
 // lock-free because each gradient is written once by its worker and read, then deleted, by the
 // server; the Future Work section asks for a better locking mechanism).  Workers and the server run
 // on two HIP streams and meet only through this state:
-//   append   a batch of workers claims consecutive positions with one atomic add on `tail`, writes its
-//            rows, then stamps each row with position + 1 (release) once the row is complete;
+//   append   a batch of workers writes its rows, then claims consecutive positions with one atomic add
+//            on `tail` and stamps each row with position + 1 (release).  The rows are the ones the
+//            host predicted from the appends it has enqueued (one worker stream: enqueue order is
+//            position order), so nothing on the device waits for the claim; a claim that does not
+//            land on the predicted rows raises `fault` and stamps nothing;
 //   consume  the server takes the longest prefix of stamped rows starting at `head` (acquire), applies
 //            it, and deletes it by advancing `head` (release).
 // A row is reused by position + capacity, whose stamp differs, so stamps are never cleared.  The host
@@ -18,34 +21,29 @@ typedef unsigned long long u64;
 
 __global__ void store_reset_kernel(StoreState* st, u64 version) { st->version = version; }
 
-__global__ __launch_bounds__(256) void store_claim_kernel(StoreBuffers sb, WorkerMeta* meta, int n)
+__global__ __launch_bounds__(256) void store_publish_kernel(StoreBuffers sb, const WorkerMeta* meta, int n)
 {
     __shared__ u64 base;
+    // everything the worker kernels wrote to the rows precedes this launch in stream order
     if (threadIdx.x == 0) base = atomicAdd(&sb.state->tail, (u64)n);
     __syncthreads();
     for (int i = threadIdx.x; i < n; i += 256) {
         const u64 pos = base + (u64)i;
-        const int q = (int)(pos % (u64)sb.cap);
         const WorkerMeta m = meta[i];
-        meta[i].q = q;
+        if ((int)(pos % (u64)sb.cap) != m.q) {
+            sb.state->fault = 1;  // same value from every lane that sees it
+            continue;
+        }
         StoreEntryMeta e;
         e.pos = pos;
         e.version = sb.ring_version[m.slot];
         e.mb = ((u64)m.mb_hi << 32) | m.mb_lo;
         e.worker = sb.worker_id[i];
         e.pad = 0;
-        sb.entry[q] = e;
+        sb.entry[m.q] = e;
+        // the release makes row and metadata visible to whoever reads the stamp with acquire
+        __hip_atomic_store(&sb.stamp[m.q], pos + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
     }
-}
-
-__global__ __launch_bounds__(256) void store_publish_kernel(StoreBuffers sb, const WorkerMeta* meta, int n)
-{
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i >= n) return;
-    const int q = meta[i].q;
-    // Everything the worker kernels wrote to row q precedes this launch in stream order; the release
-    // makes it visible to whoever reads the stamp with acquire.
-    __hip_atomic_store(&sb.stamp[q], sb.entry[q].pos + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // One wavefront: 64 stamps are tested per pass; the run of ready rows from lane 0 is taken.
@@ -100,15 +98,9 @@ hipError_t launch_store_reset(const StoreBuffers& sb, unsigned long long version
     return hipGetLastError();
 }
 
-hipError_t launch_store_claim(const StoreBuffers& sb, WorkerMeta* meta, int n, hipStream_t s)
-{
-    hipLaunchKernelGGL(store_claim_kernel, dim3(1), dim3(256), 0, s, sb, meta, n);
-    return hipGetLastError();
-}
-
 hipError_t launch_store_publish(const StoreBuffers& sb, const WorkerMeta* meta, int n, hipStream_t s)
 {
-    hipLaunchKernelGGL(store_publish_kernel, dim3((n + 255) / 256), dim3(256), 0, s, sb, meta, n);
+    hipLaunchKernelGGL(store_publish_kernel, dim3(1), dim3(256), 0, s, sb, meta, n);
     return hipGetLastError();
 }
 
