@@ -254,6 +254,29 @@ def drain_mitigated(theta: np.ndarray, pending: Sequence[np.ndarray], lr: float,
     return drain(theta, scaled, used, mode), used
 
 
+def drain_adadelta(theta: np.ndarray, pending: Sequence[np.ndarray], lr: float, rho: float, eps: float,
+                   acc_g2: np.ndarray, acc_dx2: np.ndarray):
+    """Recovery drain with an adaptive learning rate, which Section 2.3's last paragraph names as a
+    candidate for applying the stale gradients (Adadelta; the paper gives no details, so this is the
+    method as published: Zeiler 2012, Algorithm 1).  The pending gradients are applied one by one in
+    arrival order; per parameter
+        E[g^2]  <- rho E[g^2] + (1 - rho) g^2
+        dx      <- - sqrt(E[dx^2] + eps) / sqrt(E[g^2] + eps) * g
+        E[dx^2] <- rho E[dx^2] + (1 - rho) dx^2
+        theta   <- theta + lr * dx
+    Returns (theta, E[g^2], E[dx^2]) after the last gradient."""
+    theta = np.array(theta, dtype=np.float64, copy=True)
+    g2 = np.array(acc_g2, dtype=np.float64, copy=True)
+    dx2 = np.array(acc_dx2, dtype=np.float64, copy=True)
+    for g in pending:
+        g = np.asarray(g, dtype=np.float64)
+        g2 = rho * g2 + (1.0 - rho) * g * g
+        dx = -np.sqrt(dx2 + eps) / np.sqrt(g2 + eps) * g
+        dx2 = rho * dx2 + (1.0 - rho) * dx * dx
+        theta = theta + lr * dx
+    return theta, g2, dx2
+
+
 # --------------------------------------------------------------------------- server model
 
 @dataclass
@@ -341,6 +364,19 @@ class OracleServer:
         else:
             for s in seqs:
                 self.apply_async(s, lr)
+        return k
+
+    def drain_adadelta(self, lr: float, rho: float, eps: float) -> int:
+        """Recovery with Adadelta steps over the pending gradients (see drain_adadelta); the two
+        accumulators are server state, zero until first used."""
+        if not hasattr(self, "acc_g2"):
+            self.acc_g2 = np.zeros_like(self.theta)
+            self.acc_dx2 = np.zeros_like(self.theta)
+        k = len(self.pending)
+        self.theta, self.acc_g2, self.acc_dx2 = drain_adadelta(self.theta, [e.grad for e in self.pending], lr, rho, eps,
+                                                               self.acc_g2, self.acc_dx2)
+        self.version += k
+        self.pending = []
         return k
 
     def restore_weights(self, slot: int) -> int:

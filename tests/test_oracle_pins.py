@@ -503,3 +503,39 @@ def test_store_consume_is_a_prefix_in_arrival_order_read_once_then_deleted():
     a.consume(orc.DRAIN_SEQ, lr, 2), a.consume(orc.DRAIN_SEQ, lr, 1), a.consume(orc.DRAIN_SEQ, lr, 3)
     b.consume(orc.DRAIN_SEQ, lr, n)
     assert np.array_equal(a.theta, b.theta) and a.version == b.version == n
+
+
+def test_adadelta_drain_against_an_independent_library_and_closed_forms():
+    """Section 2.3 names an adaptive learning rate (Adadelta) for the stale gradients.  The oracle's
+    recursion is pinned against torch.optim.Adadelta run on the same gradient sequence in fp64, and
+    against the first step's closed form dx = -sqrt(eps) / sqrt((1 - rho) g^2 + eps) * g."""
+    import torch
+    rng = np.random.default_rng(5)
+    n, K, lr, rho, eps = 37, 9, 0.7, 0.9, 1e-6
+    theta0 = rng.standard_normal(n)
+    grads = [rng.standard_normal(n) * 10.0 ** rng.integers(-3, 2) for _ in range(K)]
+    got, g2, dx2 = orc.drain_adadelta(theta0, grads, lr, rho, eps, np.zeros(n), np.zeros(n))
+    p = torch.nn.Parameter(torch.tensor(theta0, dtype=torch.float64))
+    opt = torch.optim.Adadelta([p], lr=lr, rho=rho, eps=eps)
+    for g in grads:
+        p.grad = torch.tensor(g, dtype=torch.float64)
+        opt.step()
+    assert np.allclose(got, p.detach().numpy(), rtol=1e-12, atol=1e-14)
+    st = opt.state[p]
+    assert np.allclose(g2, st["square_avg"].numpy(), rtol=1e-12) and np.allclose(dx2, st["acc_delta"].numpy(), rtol=1e-12)
+    one, g2_1, dx2_1 = orc.drain_adadelta(theta0, grads[:1], lr, rho, eps, np.zeros(n), np.zeros(n))
+    dx = -np.sqrt(eps) / np.sqrt((1 - rho) * grads[0] ** 2 + eps) * grads[0]
+    assert np.allclose(one, theta0 + lr * dx, rtol=1e-15) and np.allclose(g2_1, (1 - rho) * grads[0] ** 2)
+    assert np.allclose(dx2_1, (1 - rho) * dx ** 2)
+    # the state carries over: two drains equal one drain of the concatenation; zero gradients move nothing
+    a, ag, ad = orc.drain_adadelta(theta0, grads[:4], lr, rho, eps, np.zeros(n), np.zeros(n))
+    b, _, _ = orc.drain_adadelta(a, grads[4:], lr, rho, eps, ag, ad)
+    assert np.array_equal(b, got)
+    z, zg, zd = orc.drain_adadelta(theta0, [np.zeros(n)] * 3, lr, rho, eps, np.zeros(n), np.zeros(n))
+    assert np.array_equal(z, theta0) and not zg.any() and not zd.any()
+    # and on the server model: version += K, queue emptied
+    s = orc.OracleServer(TINY, 7, 0.25, 1, theta0)
+    for i, g in enumerate(grads):
+        s.pending.append(orc.QueueEntry(i, 0, 0, i, g, 0.0))
+    assert s.drain_adadelta(lr, rho, eps) == K and s.version == K and not s.pending
+    assert np.array_equal(s.theta, got)
