@@ -140,6 +140,10 @@ def main():
     for r in range(ROUNDS):
         ps.worker_grads_batched(ctx, workers, slots, [synth.minibatch_id(w, 10 ** 6 + r) for w in workers], xs[r], ys[r], loss)
     ps.ps_drain_buffered_mitigated(ctx, ps.DRAIN_SEQ, LR, 256.0, 10.0)
+    # and one more, applied as Adadelta steps
+    for r in range(ROUNDS):
+        ps.worker_grads_batched(ctx, workers, slots, [synth.minibatch_id(w, 2 * 10 ** 6 + r) for w in workers], xs[r], ys[r], loss)
+    ps.ps_drain_buffered_adadelta(ctx, 1.0, 0.9, 1e-6)
     prof_mit = ps.ps_profile_read(ctx)
     ps.ps_profile_enable(ctx, False)
     final_loss = float(loss.mean().item())
@@ -225,7 +229,8 @@ def main():
         "final_mean_loss": final_loss,
     }
     mit = []
-    for name, algo in (("grad_sqnorm_kernel", W * ROUNDS * P * 4), ("apply_kernel<1, clip>", W * ROUNDS * P * 4 + 2 * P * 4)):
+    for name, algo in (("grad_sqnorm_kernel", W * ROUNDS * P * 4), ("apply_kernel<1, clip>", W * ROUNDS * P * 4 + 2 * P * 4),
+                       ("apply_adadelta_kernel", W * ROUNDS * P * 4 + 6 * P * 4)):
         ms, n = prof_mit.get(name, (0.0, 0))
         if n:
             ach = algo / (ms / n * 1e-3) / 1e9

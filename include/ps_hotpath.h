@@ -158,6 +158,15 @@ typedef struct {
 PS_API ps_status ps_drain_buffered_mitigated(ps_ctx* ctx, int32_t mode, const ps_drain_policy* policy,
                                       int32_t* n_applied_host, float* lr_used_host);
 
+/* Recovery with an adaptive learning rate, which Section 2.3 (last paragraph) names, as Adadelta, among
+ * the methods for applying the stale gradients; the paper gives no details, so this is the method as
+ * published (Zeiler 2012, Algorithm 1).  Every pending gradient g, in arrival order, is one step; per
+ * parameter:  E[g^2] := rho E[g^2] + (1-rho) g^2;  dx := -sqrt(E[dx^2] + eps) / sqrt(E[g^2] + eps) * g;
+ * E[dx^2] := rho E[dx^2] + (1-rho) dx^2;  theta := theta + lr * dx.   Version += K, queue emptied.
+ * The two accumulators are state of the context: zero after ps_init and ps_set_weights, carried from
+ * one call to the next, not part of a snapshot.  rho in [0, 1), eps > 0, else PS_EINVAL. */
+PS_API ps_status ps_drain_buffered_adadelta(ps_ctx* ctx, float lr, float rho, float eps, int32_t* n_applied_host);
+
 /* Recovery of the checkpointing and chain-replication arms (Section 2.1: the resurrected server
  * rehydrates the latest checkpoint and continues from that older state; Section 2.2: a backup server
  * with periodically replicated weights takes over): theta := ring[slot], version := the version that

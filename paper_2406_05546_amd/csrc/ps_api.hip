@@ -51,7 +51,7 @@ struct Carve {
 };
 
 struct Layout {
-    uint64_t theta, ring, queue, meta, idx, st_state, st_stamp, st_entry, st_ringver, st_log, st_range, st_idx, st_wid, p1, am1, p2, am2, ht, z, pred, d3, dp2g, part, part1, fpart, normpart, scale, eval_loss, eval_ok, keep, total;
+    uint64_t theta, ring, queue, ada_g2, ada_dx2, meta, idx, st_state, st_stamp, st_entry, st_ringver, st_log, st_range, st_idx, st_wid, p1, am1, p2, am2, ht, z, pred, d3, dp2g, part, part1, fpart, normpart, scale, eval_loss, eval_ok, keep, total;
 };
 
 bool config_ok(const ps_config* c)
@@ -68,6 +68,8 @@ Layout make_layout(const ps_config& c)
     l.theta = k.take(row);
     l.ring = k.take(row * c.n_versions);
     l.queue = k.take(row * c.queue_capacity);
+    l.ada_g2 = k.take(row);
+    l.ada_dx2 = k.take(row);
     l.meta = k.take(sizeof(WorkerMeta) * c.max_workers);
     l.idx = k.take(sizeof(int32_t) * c.queue_capacity);
     l.st_state = k.take(sizeof(StoreState));
@@ -411,6 +413,7 @@ ps_status ps_set_weights(ps_ctx* c, const float* theta_host)
         PS_HIP(c, hipMemcpyAsync(c->ring(s), c->theta(), sizeof(float) * PSTRIDE, hipMemcpyDeviceToDevice, c->stream));
         c->ring_version[s] = 0;
     }
+    PS_HIP(c, hipMemsetAsync(c->at<float>(c->lay.ada_g2), 0, 2 * sizeof(float) * PSTRIDE, c->stream));  // both accumulators
     PS_HIP(c, hipStreamSynchronize(c->stream));
     c->version = 0;
     return PS_OK;
@@ -746,6 +749,24 @@ ps_status ps_store_entry(ps_ctx* c, uint64_t position, float* grad_host, int32_t
     if (worker_host) *worker_host = e.worker;
     if (version_host) *version_host = e.version;
     if (minibatch_host) *minibatch_host = e.mb;
+    return PS_OK;
+}
+
+ps_status ps_drain_buffered_adadelta(ps_ctx* c, float lr, float rho, float eps, int32_t* n_applied_host)
+{
+    if (!c) return PS_EINVAL;
+    if (!(rho >= 0.f && rho < 1.f) || !(eps > 0.f)) return fail(c, PS_EINVAL, "ps_drain_buffered_adadelta: rho must be in [0, 1), eps > 0");
+    { const ps_status g_ = ordered_guard(c, "ps_drain_buffered_adadelta"); if (g_ != PS_OK) return g_; }
+    const std::vector<int32_t> idx = c->pending;
+    if (n_applied_host) *n_applied_host = (int32_t)idx.size();
+    if (idx.empty()) return PS_OK;
+    ps_status st = upload(c, c->at<int32_t>(c->lay.idx), idx.data(), idx.size() * sizeof(int32_t));
+    if (st != PS_OK) return st;
+    PS_HIP(c, launch_apply_adadelta(c->theta(), c->at<float>(c->lay.ada_g2), c->at<float>(c->lay.ada_dx2),
+                                    c->at<float>(c->lay.queue), c->at<int32_t>(c->lay.idx), (int)idx.size(), lr, rho, eps,
+                                    c->stream, c->prof));
+    release_entries(c, idx);
+    c->version += idx.size();
     return PS_OK;
 }
 

@@ -73,6 +73,50 @@ __global__ __launch_bounds__(256) void apply_kernel(float4* __restrict__ theta, 
     theta[i] = t;
 }
 
+// Adadelta steps over the K listed rows in order (Zeiler 2012, Algorithm 1), one pass over HBM like the
+// plain drain: a lane keeps its four weights and their two accumulators in registers while the rows
+// stream past.  The quotient sqrt(E[dx^2] + eps) / sqrt(E[g^2] + eps) is formed with the hardware's
+// square root and reciprocal square root (about 1 ulp each), which keeps the kernel bandwidth bound.
+__global__ __launch_bounds__(256) void apply_adadelta_kernel(float4* __restrict__ theta, float4* __restrict__ acc_g2,
+                                                              float4* __restrict__ acc_dx2, const float4* __restrict__ queue,
+                                                              const int32_t* __restrict__ idx, int K, float lr, float rho,
+                                                              float eps)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= ROW4) return;
+    float t[4], g2[4], dx2[4];
+    {
+        const float4 a = theta[i], b = acc_g2[i], c = acc_dx2[i];
+        t[0] = a.x; t[1] = a.y; t[2] = a.z; t[3] = a.w;
+        g2[0] = b.x; g2[1] = b.y; g2[2] = b.z; g2[3] = b.w;
+        dx2[0] = c.x; dx2[1] = c.y; dx2[2] = c.z; dx2[3] = c.w;
+    }
+    const float one_m_rho = 1.f - rho;
+    const float4* col = queue + i;
+    auto step = [&](const float4& g4) {
+        const float g[4] = {g4.x, g4.y, g4.z, g4.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            g2[e] = fmaf(rho, g2[e], one_m_rho * g[e] * g[e]);
+            const float dx = -(__builtin_amdgcn_sqrtf(dx2[e] + eps) * __builtin_amdgcn_rsqf(g2[e] + eps)) * g[e];
+            dx2[e] = fmaf(rho, dx2[e], one_m_rho * dx * dx);
+            t[e] = fmaf(lr, dx, t[e]);
+        }
+    };
+    int k = 0;
+    for (; k + UNROLL <= K; k += UNROLL) {
+        float4 g[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) g[u] = ld_stream(col + (size_t)idx[k + u] * ROW4);
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) step(g[u]);
+    }
+    for (; k < K; ++k) step(ld_stream(col + (size_t)idx[k] * ROW4));
+    theta[i] = make_float4(t[0], t[1], t[2], t[3]);
+    acc_g2[i] = make_float4(g2[0], g2[1], g2[2], g2[3]);
+    acc_dx2[i] = make_float4(dx2[0], dx2[1], dx2[2], dx2[3]);
+}
+
 // Squared 2-norm of queue rows, first pass: block (b, k) sums the squares of slice b of row idx[k]
 // (the row padding is zero) and writes one partial; fixed slices and a fixed tree keep it reproducible.
 constexpr int NORM_SLICES = 32;
@@ -143,6 +187,17 @@ hipError_t launch_apply_clipped(float* theta, const float* queue, const int32_t*
     else
         hipLaunchKernelGGL((apply_kernel<1, true>), grid, block, 0, s, (float4*)theta, (const float4*)queue, idx_dev, K, lr,
                            (const float*)scale_dev, (const uint32_t*)nullptr);
+    prof.end(s);
+    return hipGetLastError();
+}
+
+hipError_t launch_apply_adadelta(float* theta, float* acc_g2, float* acc_dx2, const float* queue, const int32_t* idx_dev,
+                                 int K, float lr, float rho, float eps, hipStream_t s, Profiler& prof)
+{
+    if (K <= 0) return hipSuccess;
+    prof.begin(K_APPLY_ADADELTA, s);
+    hipLaunchKernelGGL(apply_adadelta_kernel, dim3((ROW4 + 255) / 256), dim3(256), 0, s, (float4*)theta, (float4*)acc_g2,
+                       (float4*)acc_dx2, (const float4*)queue, idx_dev, K, lr, rho, eps);
     prof.end(s);
     return hipGetLastError();
 }

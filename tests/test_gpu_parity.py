@@ -342,6 +342,80 @@ def test_full_size_mitigated_drain_1024(ps, mode):
         ps.ps_destroy(ctx)
 
 
+def test_adadelta_recovery_small_with_carried_state(ps):
+    """Two outages recovered with Adadelta steps over real worker gradients; the accumulators carry
+    from the first recovery to the second and are cleared by ps_set_weights."""
+    W, B, lr, rho, eps = 4, 16, 1.0, 0.9, 1e-6
+    theta0 = synth.he_uniform_theta(8)
+    o = orc.OracleServer(orc.Dims(), DROP_SEED, P_DROP, 1, theta0)
+    ctx = ps.ps_init(ps.make_config(W, B, 1, 3 * W, DROP_SEED, P_DROP))
+    try:
+        ps.ps_set_weights(ctx, theta0)
+        step = 0
+        for rounds in (3, 2):
+            for _ in range(rounds):
+                mbs = [synth.minibatch_id(w, step) for w in range(W)]
+                x, y = synth.minibatches(DATA_SEED, mbs, B)
+                xd, yd = _torch_inputs(x, y)
+                entries = ps.worker_grads_batched(ctx, range(W), [0] * W, mbs, xd, yd)
+                ref = o.worker_grads_batched(range(W), [0] * W, mbs, x, y)
+                for i in range(W):
+                    if not parity.is_close(ps.ps_get_grad(ctx, entries[i]), ref[i].grad, parity.GRAD_TOL):
+                        ref[i].grad[:] = parity.check_worker(ps, ctx, i, entries[i], o.ring[0], x[i], y[i], mbs[i], DROP_SEED,
+                                                             P_DROP, f"step {step} worker {i}")["grad"]
+                step += 1
+            assert ps.ps_drain_buffered_adadelta(ctx, lr, rho, eps) == rounds * W
+            assert o.drain_adadelta(lr, rho, eps) == rounds * W
+            parity.assert_close(ps.ps_get_weights(ctx), o.theta, parity.WEIGHT_TOL, "weights after Adadelta recovery")
+            assert ps.ps_version(ctx) == o.version and ps.ps_queue_meta(ctx) == []
+            ps.ps_snapshot_weights(ctx, 0)
+            o.snapshot_weights(0)
+        moved = np.abs(o.theta - theta0).max()
+        assert moved > 1e-3 and np.abs(ps.ps_get_weights(ctx) - o.theta).max() <= 1e-3 * moved
+        assert ps.ps_drain_buffered_adadelta(ctx, lr, rho, eps) == 0            # nothing pending: nothing changes
+        # ps_set_weights clears the accumulators: the same single gradient then gives the first-step closed form
+        ps.ps_set_weights(ctx, theta0)
+        g = synth.gradient_rows(3, 0, 1, ps.P)[0]
+        ps.ps_queue_push_host(ctx, g, 0, 0, 0)
+        assert ps.ps_drain_buffered_adadelta(ctx, lr, rho, eps) == 1
+        one, _, _ = orc.drain_adadelta(theta0, [g], lr, rho, eps, np.zeros(ps.P), np.zeros(ps.P))
+        parity.assert_close(ps.ps_get_weights(ctx), one, parity.WEIGHT_TOL, "first Adadelta step after a reset")
+        for bad in ((1.0, 1e-6), (-0.1, 1e-6), (0.9, 0.0)):
+            with pytest.raises(ps.PsError) as err:
+                ps.ps_drain_buffered_adadelta(ctx, lr, *bad)
+            assert err.value.status == ps.PS_EINVAL
+    finally:
+        ps.ps_destroy(ctx)
+
+
+def test_full_size_adadelta_drain_1024(ps):
+    """The 3.3 GB backlog applied as 1024 Adadelta steps, then 64 more with the carried accumulators."""
+    K, lr, rho, eps = 1024, 1.0, 0.95, 1e-6
+    theta0 = synth.he_uniform_theta(3)
+    ctx = ps.ps_init(ps.make_config(1, 1, 1, K, DROP_SEED, P_DROP))
+    try:
+        ps.ps_set_weights(ctx, theta0)
+        ref, g2, dx2 = theta0.astype(np.float64), np.zeros(ps.P), np.zeros(ps.P)
+        for k0 in range(0, K + 64, 64):
+            if k0 == K:
+                say("adadelta_1024: draining 1024 rows")
+                assert ps.ps_drain_buffered_adadelta(ctx, lr, rho, eps) == K
+                got = ps.ps_get_weights(ctx)
+                parity.assert_close(got, ref, parity.WEIGHT_TOL, "Adadelta drain")
+                assert np.abs(got - ref).max() <= 1e-3 * np.abs(ref - theta0).max()
+            rows = synth.gradient_rows(29, k0, 64, ps.P)
+            rows *= np.array([0.1, 1.0, 10.0], np.float32)[(k0 + np.arange(64)) % 3][:, None]
+            for i in range(64):
+                ps.ps_queue_push_host(ctx, rows[i], 0, 0, k0 + i)
+            ref, g2, dx2 = orc.drain_adadelta(ref, list(rows), lr, rho, eps, g2, dx2)
+        assert ps.ps_drain_buffered_adadelta(ctx, lr, rho, eps) == 64 and ps.ps_version(ctx) == K + 64
+        got = ps.ps_get_weights(ctx)
+        parity.assert_close(got, ref, parity.WEIGHT_TOL, "Adadelta drain with carried accumulators")
+        assert np.abs(got - ref).max() <= 1e-3 * np.abs(ref - theta0).max()
+    finally:
+        ps.ps_destroy(ctx)
+
+
 # ------------------------------------------------------------------ edges and errors
 
 def test_edges_and_error_codes(ps):
