@@ -277,6 +277,25 @@ def drain_adadelta(theta: np.ndarray, pending: Sequence[np.ndarray], lr: float, 
     return theta, g2, dx2
 
 
+def elastic_average(centre: np.ndarray, locals_: Sequence[np.ndarray], alpha: float):
+    """One synchronous elastic-averaging step (Zhang, Choromanska, LeCun 2015, "Deep learning with
+    elastic averaging SGD", the update of its Section 2 with alpha = eta * rho), which Section 2.3's
+    last paragraph names among the methods to try for the work done while the server was away:
+    worker-local weights x_i and the centre are pulled towards each other,
+        x_i     <- x_i - alpha (x_i - centre)
+        centre  <- centre + alpha sum_i (x_i - centre)
+    with every difference taken before the update.  Returns (new centre, list of new x_i)."""
+    c = np.asarray(centre, dtype=np.float64)
+    xs = [np.asarray(x, dtype=np.float64) for x in locals_]
+    total = np.zeros_like(c)
+    out = []
+    for x in xs:
+        d = x - c
+        out.append(x - alpha * d)
+        total = total + d
+    return c + alpha * total, out
+
+
 # --------------------------------------------------------------------------- server model
 
 @dataclass
@@ -365,6 +384,18 @@ class OracleServer:
             for s in seqs:
                 self.apply_async(s, lr)
         return k
+
+    def apply_local(self, slot: int, seq: int, lr: float) -> None:
+        """A worker that trains on its own copy of the weights (elastic averaging SGD): plain SGD
+        step on ring slot `slot` with one pending gradient; the server's weights do not change."""
+        (e,) = self._take([seq])
+        self.ring[slot] = apply_async(self.ring[slot], e.grad, lr)
+
+    def elastic_average(self, slots: Sequence[int], alpha: float) -> None:
+        self.theta, new = elastic_average(self.theta, [self.ring[s] for s in slots], alpha)
+        for s, x in zip(slots, new):
+            self.ring[s] = x
+        self.version += 1
 
     def drain_adadelta(self, lr: float, rho: float, eps: float) -> int:
         """Recovery with Adadelta steps over the pending gradients (see drain_adadelta); the two

@@ -539,3 +539,34 @@ def test_adadelta_drain_against_an_independent_library_and_closed_forms():
         s.pending.append(orc.QueueEntry(i, 0, 0, i, g, 0.0))
     assert s.drain_adadelta(lr, rho, eps) == K and s.version == K and not s.pending
     assert np.array_equal(s.theta, got)
+
+
+def test_elastic_averaging_step_invariants_and_closed_forms():
+    """Elastic averaging SGD (Section 2.3 names it): the forces between centre and workers cancel, so
+    centre + sum_i x_i is conserved; equal weights are a fixed point; one worker with alpha = 1/2
+    meets the centre half way; differences follow (x_i - c)' = (1 - alpha)(x_i - c) - alpha sum_j (x_j - c)."""
+    rng = np.random.default_rng(2)
+    n, W, alpha = 11, 5, 0.07
+    c = rng.standard_normal(n)
+    xs = [rng.standard_normal(n) for _ in range(W)]
+    c1, xs1 = orc.elastic_average(c, xs, alpha)
+    assert np.allclose(c1 + sum(xs1), c + sum(xs), rtol=0, atol=1e-13)
+    tot = sum(x - c for x in xs)
+    for x, x1 in zip(xs, xs1):
+        assert np.allclose(x1 - c1, (1 - alpha) * (x - c) - alpha * tot, rtol=0, atol=1e-13)
+    same_c, same = orc.elastic_average(c, [c.copy()] * 3, 0.3)
+    assert np.array_equal(same_c, c) and all(np.array_equal(x, c) for x in same)
+    mid_c, (mid_x,) = orc.elastic_average(c, [xs[0]], 0.5)
+    assert np.allclose(mid_c, (c + xs[0]) / 2) and np.allclose(mid_x, (c + xs[0]) / 2)
+    zero_c, zero = orc.elastic_average(c, xs, 0.0)
+    assert np.array_equal(zero_c, c) and all(np.array_equal(a, b) for a, b in zip(zero, xs))
+    # on the server model: a local step touches only its slot; the elastic step counts as one update
+    s = orc.OracleServer(TINY, 7, 0.25, 2, c)
+    g = rng.standard_normal(n)
+    s.pending.append(orc.QueueEntry(0, 1, 0, 0, g, 0.0))
+    s.next_seq = 1
+    s.apply_local(1, 0, 0.1)
+    assert np.array_equal(s.theta, c) and np.array_equal(s.ring[0], c) and np.allclose(s.ring[1], c - 0.1 * g)
+    assert not s.pending and s.version == 0
+    s.elastic_average([0, 1], 0.25)
+    assert s.version == 1 and np.allclose(s.theta + s.ring[0] + s.ring[1], 3 * c - 0.1 * g)
