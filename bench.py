@@ -183,6 +183,16 @@ def main():
     assert st["claimed"] == st["consumed"] == (n_ov + 1) * W * ROUNDS and np.isfinite(ps.ps_get_weights(ctx)).all()
     ps.ps_destroy(ctx)
 
+    # outside the timed region: one elastic-averaging step over 256 worker-local copies of the weights
+    ctx_e = ps.ps_init(ps.make_config(1, 1, W, 1, 0xD0D0, 0.25), dev)
+    ps.ps_set_weights(ctx_e, synth.he_uniform_theta(1))
+    ps.ps_elastic_average(ctx_e, list(range(W)), 1.0 / 512)
+    ps.ps_profile_enable(ctx_e, True)
+    for _ in range(4):
+        ps.ps_elastic_average(ctx_e, list(range(W)), 1.0 / 512)
+    prof_el = ps.ps_profile_read(ctx_e)
+    ps.ps_destroy(ctx_e)
+
     images_per_step = W * B * ROUNDS
     n_launch_images = W * B
     kernels = []
@@ -237,6 +247,13 @@ def main():
             mit.append({"kernel": name, "avg_ms": ms / n, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBPS,
                         "unit": "GB/s", "frac": ach / PEAK_HBM_GBPS, "algorithmic_bytes": algo})
     out["drain_mitigated"] = mit
+    ms, n = prof_el.get("elastic_average_kernel", (0.0, 0))
+    if n:
+        algo = (2 * W + 2) * P * 4
+        ach = algo / (ms / n * 1e-3) / 1e9
+        out["elastic_average"] = {"kernel": "elastic_average_kernel", "local_copies": W, "avg_ms": ms / n, "bound": "hbm",
+                                  "achieved": ach, "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBPS,
+                                  "algorithmic_bytes": algo}
     out["lockfree_store"] = {
         "schedule": f"{ROUNDS} x (append W={W} on the worker stream; SEQ server step over the 256 new rows on the server "
                     "stream) -> publish into the other ring slot; same updates in the same order as the ordered SEQ drain",

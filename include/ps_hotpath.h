@@ -167,6 +167,20 @@ PS_API ps_status ps_drain_buffered_mitigated(ps_ctx* ctx, int32_t mode, const ps
  * one call to the next, not part of a snapshot.  rho in [0, 1), eps > 0, else PS_EINVAL. */
 PS_API ps_status ps_drain_buffered_adadelta(ps_ctx* ctx, float lr, float rho, float eps, int32_t* n_applied_host);
 
+/* Elastic averaging SGD (Zhang, Choromanska, LeCun 2015), which Section 2.3 (last paragraph) names
+ * among the methods to try for the work workers do while the server is away.  Here a worker's local
+ * weights are a ring slot of its own: it computes its gradient there (worker_grads_batched with that
+ * slot) and takes a plain SGD step on its own copy,
+ *   ps_apply_local:      ring[slot_i] := ring[slot_i] - lr * g(queue_index_i)   for i in [0, n)
+ * (distinct slots, pending entries, which are then freed; the server's weights and the version do not
+ * change), and from time to time, or when the server is back, one synchronous elastic step couples
+ * the n listed local copies to the server's weights (the centre), every difference taken first:
+ *   ps_elastic_average:  d_i = ring[slot_i] - theta;  ring[slot_i] := ring[slot_i] - alpha * d_i;
+ *                        theta := theta + alpha * (d_0 + ... + d_{n-1});  version += 1
+ * (alpha = the paper's eta * rho; distinct slots; alpha >= 0).  n = 0 is a no-op in both. */
+PS_API ps_status ps_apply_local(ps_ctx* ctx, int32_t n, const int32_t* slot_host, const int32_t* queue_index_host, float lr);
+PS_API ps_status ps_elastic_average(ps_ctx* ctx, const int32_t* slot_host, int32_t n, float alpha);
+
 /* Recovery of the checkpointing and chain-replication arms (Section 2.1: the resurrected server
  * rehydrates the latest checkpoint and continues from that older state; Section 2.2: a backup server
  * with periodically replicated weights takes over): theta := ring[slot], version := the version that

@@ -27,7 +27,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libps_hotpa
 
 EXPORTS = ["ps_workspace_bytes", "ps_init", "ps_destroy", "ps_sync", "ps_set_weights", "ps_get_weights",
            "ps_snapshot_weights", "worker_grads_batched", "ps_queue_push_host", "ps_apply_sync", "ps_apply_async",
-           "ps_drain_buffered", "ps_drain_buffered_mitigated", "ps_drain_buffered_adadelta", "ps_restore_weights", "ps_evaluate",
+           "ps_drain_buffered", "ps_drain_buffered_mitigated", "ps_drain_buffered_adadelta", "ps_apply_local", "ps_elastic_average", "ps_restore_weights", "ps_evaluate",
            "worker_grads_append", "ps_store_consume", "ps_store_publish", "ps_store_state", "ps_store_steps",
            "ps_store_entry", "ps_get_grad", "ps_queue_meta", "ps_version", "ps_debug_last_batch", "ps_profile_enable",
            "ps_profile_read", "ps_profile_kernel_count", "ps_profile_kernel_name", "ps_last_error"]
@@ -82,6 +82,8 @@ def load_library() -> ctypes.CDLL:
             "ps_drain_buffered_mitigated": [vp, i32, ctypes.POINTER(ps_drain_policy), ctypes.POINTER(i32),
                                             ctypes.POINTER(f32)],
             "ps_drain_buffered_adadelta": [vp, f32, f32, f32, ctypes.POINTER(i32)],
+            "ps_apply_local": [vp, i32, vp, vp, f32],
+            "ps_elastic_average": [vp, vp, i32, f32],
             "ps_restore_weights": [vp, i32, ctypes.POINTER(i32)],
             "ps_evaluate": [vp, i32, i32, vp, vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double), vp],
             "worker_grads_append": [vp, i32, vp, vp, vp, vp, vp, vp],
@@ -255,6 +257,17 @@ def ps_drain_buffered_adadelta(ctx: Context, lr: float, rho: float, eps: float) 
     k = ctypes.c_int32(0)
     _check(ctx, "ps_drain_buffered_adadelta", load_library().ps_drain_buffered_adadelta(ctx.handle, lr, rho, eps, ctypes.byref(k)))
     return int(k.value)
+
+
+def ps_apply_local(ctx: Context, slot: Sequence[int], queue_index: Sequence[int], lr: float) -> None:
+    s, q = _np(slot, np.int32), _np(queue_index, np.int32)
+    assert s.shape == q.shape
+    _check(ctx, "ps_apply_local", load_library().ps_apply_local(ctx.handle, len(s), _vp(s), _vp(q), lr))
+
+
+def ps_elastic_average(ctx: Context, slot: Sequence[int], alpha: float) -> None:
+    s = _np(slot, np.int32)
+    _check(ctx, "ps_elastic_average", load_library().ps_elastic_average(ctx.handle, _vp(s), len(s), alpha))
 
 
 def ps_restore_weights(ctx: Context, slot: int) -> int:

@@ -51,7 +51,7 @@ struct Carve {
 };
 
 struct Layout {
-    uint64_t theta, ring, queue, ada_g2, ada_dx2, meta, idx, st_state, st_stamp, st_entry, st_ringver, st_log, st_range, st_idx, st_wid, p1, am1, p2, am2, ht, z, pred, d3, dp2g, part, part1, fpart, normpart, scale, eval_loss, eval_ok, keep, total;
+    uint64_t theta, ring, queue, ada_g2, ada_dx2, meta, idx, slotq, st_state, st_stamp, st_entry, st_ringver, st_log, st_range, st_idx, st_wid, p1, am1, p2, am2, ht, z, pred, d3, dp2g, part, part1, fpart, normpart, scale, eval_loss, eval_ok, keep, total;
 };
 
 bool config_ok(const ps_config* c)
@@ -72,6 +72,7 @@ Layout make_layout(const ps_config& c)
     l.ada_dx2 = k.take(row);
     l.meta = k.take(sizeof(WorkerMeta) * c.max_workers);
     l.idx = k.take(sizeof(int32_t) * c.queue_capacity);
+    l.slotq = k.take(2 * sizeof(int32_t) * c.n_versions);
     l.st_state = k.take(sizeof(StoreState));
     l.st_stamp = k.take(sizeof(unsigned long long) * c.queue_capacity);
     l.st_entry = k.take(sizeof(StoreEntryMeta) * c.queue_capacity);
@@ -749,6 +750,52 @@ ps_status ps_store_entry(ps_ctx* c, uint64_t position, float* grad_host, int32_t
     if (worker_host) *worker_host = e.worker;
     if (version_host) *version_host = e.version;
     if (minibatch_host) *minibatch_host = e.mb;
+    return PS_OK;
+}
+
+ps_status ps_apply_local(ps_ctx* c, int32_t n, const int32_t* slot_host, const int32_t* queue_index_host, float lr)
+{
+    if (!c) return PS_EINVAL;
+    if (n == 0) return PS_OK;
+    if (n < 0 || !slot_host || !queue_index_host) return fail(c, PS_EINVAL, "ps_apply_local: bad arguments");
+    std::vector<char> slot_seen(c->cfg.n_versions, 0), q_seen(c->cfg.queue_capacity, 0);
+    std::vector<int32_t> pairs(2 * (size_t)n), idx(n);
+    for (int i = 0; i < n; ++i) {
+        const int32_t s = slot_host[i], q = queue_index_host[i];
+        if (s < 0 || s >= c->cfg.n_versions || slot_seen[s]) return fail(c, PS_EINVAL, "ps_apply_local: slot out of range or listed twice");
+        if (q < 0 || q >= c->cfg.queue_capacity) return fail(c, PS_EINVAL, "ps_apply_local: queue index out of range");
+        if (!c->entries[q].pending || q_seen[q]) return fail(c, PS_ESTATE, "ps_apply_local: entry not pending or listed twice");
+        slot_seen[s] = q_seen[q] = 1;
+        pairs[2 * i] = s;
+        pairs[2 * i + 1] = q;
+        idx[i] = q;
+    }
+    { const ps_status g_ = ordered_guard(c, "ps_apply_local"); if (g_ != PS_OK) return g_; }
+    ps_status st = upload(c, c->at<int32_t>(c->lay.slotq), pairs.data(), pairs.size() * sizeof(int32_t));
+    if (st != PS_OK) return st;
+    PS_HIP(c, launch_local_steps(c->at<float>(c->lay.ring), c->at<float>(c->lay.queue), c->at<int32_t>(c->lay.slotq), n, lr,
+                                 c->stream, c->prof));
+    release_entries(c, idx);
+    return PS_OK;
+}
+
+ps_status ps_elastic_average(ps_ctx* c, const int32_t* slot_host, int32_t n, float alpha)
+{
+    if (!c) return PS_EINVAL;
+    if (n == 0) return PS_OK;
+    if (n < 0 || !slot_host || !(alpha >= 0.f)) return fail(c, PS_EINVAL, "ps_elastic_average: bad arguments");
+    std::vector<char> seen(c->cfg.n_versions, 0);
+    for (int i = 0; i < n; ++i) {
+        const int32_t s = slot_host[i];
+        if (s < 0 || s >= c->cfg.n_versions || seen[s]) return fail(c, PS_EINVAL, "ps_elastic_average: slot out of range or listed twice");
+        seen[s] = 1;
+    }
+    { const ps_status g_ = ordered_guard(c, "ps_elastic_average"); if (g_ != PS_OK) return g_; }
+    ps_status st = upload(c, c->at<int32_t>(c->lay.slotq), slot_host, (size_t)n * sizeof(int32_t));
+    if (st != PS_OK) return st;
+    PS_HIP(c, launch_elastic_average(c->theta(), c->at<float>(c->lay.ring), c->at<int32_t>(c->lay.slotq), n, alpha, c->stream,
+                                     c->prof));
+    c->version += 1;
     return PS_OK;
 }
 

@@ -117,6 +117,54 @@ __global__ __launch_bounds__(256) void apply_adadelta_kernel(float4* __restrict_
     acc_dx2[i] = make_float4(dx2[0], dx2[1], dx2[2], dx2[3]);
 }
 
+// Worker-local SGD steps (elastic averaging SGD: every worker trains on its own copy of the weights):
+// block row j does ring[slot_j] -= lr * queue[q_j] for the pair (slot_j, q_j); slots are distinct.
+__global__ __launch_bounds__(256) void local_step_kernel(float4* __restrict__ ring, const float4* __restrict__ queue,
+                                                          const int2* __restrict__ pairs, float lr)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= ROW4) return;
+    const int2 p = pairs[blockIdx.y];
+    float4* x = ring + (size_t)p.x * ROW4 + i;
+    const float4 g = ld_stream(queue + (size_t)p.y * ROW4 + i);
+    float4 t = *x;
+    t.x = fmaf(-lr, g.x, t.x); t.y = fmaf(-lr, g.y, t.y); t.z = fmaf(-lr, g.z, t.z); t.w = fmaf(-lr, g.w, t.w);
+    *x = t;
+}
+
+// One synchronous elastic-averaging step (Zhang et al. 2015, Section 2): with d_k = ring[slot_k] - theta,
+// all against the old theta, ring[slot_k] -= alpha d_k and theta += alpha sum_k d_k (summed in list
+// order).  One pass: a lane keeps its four centre weights while the n local copies stream through.
+__global__ __launch_bounds__(256) void elastic_average_kernel(float4* __restrict__ theta, float4* __restrict__ ring,
+                                                               const int32_t* __restrict__ slots, int n, float alpha)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= ROW4) return;
+    const float4 c = theta[i];
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    int k = 0;
+    for (; k + UNROLL <= n; k += UNROLL) {
+        float4 x[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) x[u] = ring[(size_t)slots[k + u] * ROW4 + i];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const float4 d = make_float4(x[u].x - c.x, x[u].y - c.y, x[u].z - c.z, x[u].w - c.w);
+            s.x += d.x; s.y += d.y; s.z += d.z; s.w += d.w;
+            ring[(size_t)slots[k + u] * ROW4 + i] =
+                make_float4(fmaf(-alpha, d.x, x[u].x), fmaf(-alpha, d.y, x[u].y), fmaf(-alpha, d.z, x[u].z), fmaf(-alpha, d.w, x[u].w));
+        }
+    }
+    for (; k < n; ++k) {
+        float4* px = ring + (size_t)slots[k] * ROW4 + i;
+        const float4 x = *px;
+        const float4 d = make_float4(x.x - c.x, x.y - c.y, x.z - c.z, x.w - c.w);
+        s.x += d.x; s.y += d.y; s.z += d.z; s.w += d.w;
+        *px = make_float4(fmaf(-alpha, d.x, x.x), fmaf(-alpha, d.y, x.y), fmaf(-alpha, d.z, x.z), fmaf(-alpha, d.w, x.w));
+    }
+    theta[i] = make_float4(fmaf(alpha, s.x, c.x), fmaf(alpha, s.y, c.y), fmaf(alpha, s.z, c.z), fmaf(alpha, s.w, c.w));
+}
+
 // Squared 2-norm of queue rows, first pass: block (b, k) sums the squares of slice b of row idx[k]
 // (the row padding is zero) and writes one partial; fixed slices and a fixed tree keep it reproducible.
 constexpr int NORM_SLICES = 32;
@@ -198,6 +246,28 @@ hipError_t launch_apply_adadelta(float* theta, float* acc_g2, float* acc_dx2, co
     prof.begin(K_APPLY_ADADELTA, s);
     hipLaunchKernelGGL(apply_adadelta_kernel, dim3((ROW4 + 255) / 256), dim3(256), 0, s, (float4*)theta, (float4*)acc_g2,
                        (float4*)acc_dx2, (const float4*)queue, idx_dev, K, lr, rho, eps);
+    prof.end(s);
+    return hipGetLastError();
+}
+
+hipError_t launch_local_steps(float* ring, const float* queue, const int32_t* pairs_dev, int n, float lr, hipStream_t s,
+                              Profiler& prof)
+{
+    if (n <= 0) return hipSuccess;
+    prof.begin(K_LOCAL_STEP, s);
+    hipLaunchKernelGGL(local_step_kernel, dim3((ROW4 + 255) / 256, n), dim3(256), 0, s, (float4*)ring, (const float4*)queue,
+                       (const int2*)pairs_dev, lr);
+    prof.end(s);
+    return hipGetLastError();
+}
+
+hipError_t launch_elastic_average(float* theta, float* ring, const int32_t* slots_dev, int n, float alpha, hipStream_t s,
+                                  Profiler& prof)
+{
+    if (n <= 0) return hipSuccess;
+    prof.begin(K_ELASTIC, s);
+    hipLaunchKernelGGL(elastic_average_kernel, dim3((ROW4 + 255) / 256), dim3(256), 0, s, (float4*)theta, (float4*)ring,
+                       slots_dev, n, alpha);
     prof.end(s);
     return hipGetLastError();
 }

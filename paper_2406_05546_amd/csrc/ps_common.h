@@ -100,7 +100,8 @@ void launch_conv2_dw(const WorkerBuffers& wb, hipStream_t s);
 // Kernels of the path, in launch order; ids index the per-kernel timing table.
 enum KernelId {
     K_CONV1_FWD, K_CONV2_FWD, K_FC1_FWD, K_FC2, K_FC1_DW, K_FC1_DX, K_CONV2_DW, K_CONV2_DX,
-    K_GRAD_REDUCE, K_APPLY_SUM, K_APPLY_SEQ, K_GRAD_SQNORM, K_APPLY_SUM_CLIP, K_APPLY_SEQ_CLIP, K_APPLY_ADADELTA, K_COUNT
+    K_GRAD_REDUCE, K_APPLY_SUM, K_APPLY_SEQ, K_GRAD_SQNORM, K_APPLY_SUM_CLIP, K_APPLY_SEQ_CLIP, K_APPLY_ADADELTA, K_LOCAL_STEP,
+    K_ELASTIC, K_COUNT
 };
 const char* kernel_name(int id);
 
@@ -138,6 +139,13 @@ hipError_t launch_apply(float* theta, const float* queue, const int32_t* idx_dev
 hipError_t launch_apply_clipped(float* theta, const float* queue, const int32_t* idx_dev, int K, float lr, int mode,
                                 float clip, float* partial_dev, float* scale_dev, hipStream_t s, Profiler& prof);
 int norm_slices();
+
+// ring[slot_j] -= lr * queue[q_j] for n (slot, q) pairs with distinct slots (pairs_dev: 2n int32).
+hipError_t launch_local_steps(float* ring, const float* queue, const int32_t* pairs_dev, int n, float lr, hipStream_t s,
+                              Profiler& prof);
+// One elastic-averaging step between theta and the n listed (distinct) ring slots.
+hipError_t launch_elastic_average(float* theta, float* ring, const int32_t* slots_dev, int n, float alpha, hipStream_t s,
+                                  Profiler& prof);
 
 // K Adadelta steps, one per listed queue row in order; acc_g2 and acc_dx2 are P-vector rows of state.
 hipError_t launch_apply_adadelta(float* theta, float* acc_g2, float* acc_dx2, const float* queue, const int32_t* idx_dev,

@@ -97,7 +97,8 @@ const char* kernel_name(int id)
         "conv1_fwd_kernel", "conv2_fwd_kernel", "gemm_f32_mfma<Fc1FwdEpi>", "fc2_kernel",
         "gemm_f32_mfma<Fc1DwEpi>", "gemm_f32_mfma<Fc1DxEpi>", "conv2_dw_kernel",
         "conv2_dx_kernel", "grad_reduce_kernel", "apply_kernel<0>", "apply_kernel<1>", "grad_sqnorm_kernel",
-        "apply_kernel<0, clip>", "apply_kernel<1, clip>", "apply_adadelta_kernel"};
+        "apply_kernel<0, clip>", "apply_kernel<1, clip>", "apply_adadelta_kernel", "local_step_kernel",
+        "elastic_average_kernel"};
     return id >= 0 && id < K_COUNT ? names[id] : "";
 }
 

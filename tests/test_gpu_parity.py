@@ -416,6 +416,95 @@ def test_full_size_adadelta_drain_1024(ps):
         ps.ps_destroy(ctx)
 
 
+def test_elastic_averaging_with_worker_local_weights(ps):
+    """Elastic averaging SGD: four workers train on their own ring slots while the server is away
+    (gradient at the own slot, local SGD step), elastic steps couple them to the centre afterwards;
+    every slot and the centre against the oracle after every elastic step."""
+    W, B, lr, alpha = 4, 16, 0.05, 0.2
+    theta0 = synth.he_uniform_theta(14)
+    o = orc.OracleServer(orc.Dims(), DROP_SEED, P_DROP, W, theta0)
+    ctx = ps.ps_init(ps.make_config(W, B, W, W, DROP_SEED, P_DROP))
+    slots = list(range(W))
+    try:
+        ps.ps_set_weights(ctx, theta0)
+        step = 0
+        for rounds, n_elastic in ((3, 2), (2, 1)):
+            for _ in range(rounds):
+                mbs = [synth.minibatch_id(w, step) for w in range(W)]
+                x, y = synth.minibatches(DATA_SEED, mbs, B)
+                xd, yd = _torch_inputs(x, y)
+                entries = ps.worker_grads_batched(ctx, range(W), slots, mbs, xd, yd)
+                ref = o.worker_grads_batched(range(W), slots, mbs, x, y)
+                for i in range(W):
+                    if not parity.is_close(ps.ps_get_grad(ctx, entries[i]), ref[i].grad, parity.GRAD_TOL):
+                        ref[i].grad[:] = parity.check_worker(ps, ctx, i, entries[i], o.ring[i], x[i], y[i], mbs[i], DROP_SEED,
+                                                             P_DROP, f"step {step} worker {i}")["grad"]
+                ps.ps_apply_local(ctx, slots, entries, lr)
+                for i in range(W):
+                    o.apply_local(i, ref[i].seq, lr)
+                assert ps.ps_queue_meta(ctx) == [] and ps.ps_version(ctx) == o.version
+                step += 1
+            assert not np.array_equal(ps.ps_get_weights(ctx, 0), ps.ps_get_weights(ctx, 1))   # the copies drift apart
+            for _ in range(n_elastic):
+                before = ps.ps_get_weights(ctx).astype(np.float64) + sum(ps.ps_get_weights(ctx, s).astype(np.float64) for s in slots)
+                ps.ps_elastic_average(ctx, slots, alpha)
+                o.elastic_average(slots, alpha)
+                centre = ps.ps_get_weights(ctx)
+                parity.assert_close(centre, o.theta, parity.WEIGHT_TOL, "centre after an elastic step")
+                after = centre.astype(np.float64)
+                for s_ in slots:
+                    local = ps.ps_get_weights(ctx, s_)
+                    parity.assert_close(local, o.ring[s_], parity.WEIGHT_TOL, f"local weights {s_} after an elastic step")
+                    after += local
+                assert np.abs(after - before).max() <= 1e-5                  # the elastic forces cancel
+                assert ps.ps_version(ctx) == o.version
+        assert np.abs(o.theta - theta0).max() > 1e-4                         # the centre did move
+        for bad in (lambda: ps.ps_elastic_average(ctx, [0, 0], alpha), lambda: ps.ps_elastic_average(ctx, [W], alpha),
+                    lambda: ps.ps_elastic_average(ctx, [0], -0.1), lambda: ps.ps_apply_local(ctx, [0], [W + 5], lr)):
+            with pytest.raises(ps.PsError) as err:
+                bad()
+            assert err.value.status == ps.PS_EINVAL
+        with pytest.raises(ps.PsError) as err:
+            ps.ps_apply_local(ctx, [0], [0], lr)                              # entry not pending
+        assert err.value.status == ps.PS_ESTATE
+    finally:
+        ps.ps_destroy(ctx)
+
+
+def test_full_size_elastic_average_256_local_copies(ps):
+    """256 worker-local copies (832 MB of ring) made different by local steps with stand-in gradient
+    rows, then one elastic step over all of them: centre and sampled copies against the oracle."""
+    W, lr, alpha = 256, 0.5, 1.0 / 512
+    theta0 = synth.he_uniform_theta(3)
+    ctx = ps.ps_init(ps.make_config(1, 1, W, W, DROP_SEED, P_DROP))
+    try:
+        ps.ps_set_weights(ctx, theta0)
+        c = theta0.astype(np.float64)
+        total = np.zeros_like(c)
+        locals_ = {}
+        entries = []
+        for k0 in range(0, W, 64):
+            rows = synth.gradient_rows(31, k0, 64, ps.P)
+            for i in range(64):
+                entries.append(ps.ps_queue_push_host(ctx, rows[i], 0, 0, k0 + i))
+                x = orc.apply_async(c, rows[i], lr)
+                total += x - c
+                if (k0 + i) in (0, 77, 255):
+                    locals_[k0 + i] = x
+        say("elastic_256: local steps and one elastic step")
+        ps.ps_apply_local(ctx, list(range(W)), entries, lr)
+        for s_, x in locals_.items():
+            parity.assert_close(ps.ps_get_weights(ctx, s_), x, parity.WEIGHT_TOL, f"local copy {s_}")
+        ps.ps_elastic_average(ctx, list(range(W)), alpha)
+        parity.assert_close(ps.ps_get_weights(ctx), c + alpha * total, parity.WEIGHT_TOL, "centre")
+        assert np.abs(ps.ps_get_weights(ctx) - (c + alpha * total)).max() <= 1e-3 * np.abs(alpha * total).max()
+        for s_, x in locals_.items():
+            parity.assert_close(ps.ps_get_weights(ctx, s_), x - alpha * (x - c), parity.WEIGHT_TOL, f"local copy {s_} after")
+        assert ps.ps_version(ctx) == 1 and ps.ps_queue_meta(ctx) == []
+    finally:
+        ps.ps_destroy(ctx)
+
+
 # ------------------------------------------------------------------ edges and errors
 
 def test_edges_and_error_codes(ps):

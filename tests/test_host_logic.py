@@ -15,7 +15,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "ps_hotpath.h")).read()
     declared = re.findall(r"^PS_API\s+[\w\s\*]+?\b(\w+)\(", header, flags=re.M)
-    assert sorted(declared) == sorted(ps.EXPORTS) and len(declared) == 31
+    assert sorted(declared) == sorted(ps.EXPORTS) and len(declared) == 33
     lib = ps.load_library()
     for name in declared:
         assert getattr(lib, name) is not None
@@ -41,7 +41,7 @@ def test_workspace_bytes_and_argument_checks_without_a_gpu():
     assert lib.ps_sync(None) == ps.PS_EINVAL and lib.ps_destroy(None) == ps.PS_EINVAL
     assert lib.ps_last_error(None) == b""
     names = [lib.ps_profile_kernel_name(k).decode() for k in range(lib.ps_profile_kernel_count())]
-    assert len(names) == 15 and len(set(names)) == 15 and lib.ps_profile_kernel_name(99) == b""
+    assert len(names) == 17 and len(set(names)) == 17 and lib.ps_profile_kernel_name(99) == b""
 
 
 def test_minibatches_depend_only_on_logical_ids():
