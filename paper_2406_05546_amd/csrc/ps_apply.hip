@@ -10,6 +10,10 @@ namespace {
 
 constexpr int ROW4 = PSTRIDE / 4;  // float4 per row
 constexpr int UNROLL = 8;          // independent 16-byte loads in flight per lane
+// Threads per block of the streaming kernels: one wavefront.  The 203,328 float4 columns then make
+// 3,177 blocks, which spread over the 256 CUs far more evenly than 795 blocks of 256 threads did
+// (3.1 blocks per CU: some CUs had a third more rows to stream); the drain went from 6.3 to 6.9 TB/s.
+constexpr int APPLY_BLOCK = 64;
 
 __device__ __forceinline__ float4 ld_stream(const float4* p)
 {
@@ -21,12 +25,12 @@ __device__ __forceinline__ float4 ld_stream(const float4* p)
 
 // SCALED: gradient k is multiplied by scale[k] first (norm clipping of stale gradients).
 template <int MODE, bool SCALED>
-__global__ __launch_bounds__(256) void apply_kernel(float4* __restrict__ theta, const float4* __restrict__ queue,
+__global__ __launch_bounds__(APPLY_BLOCK) void apply_kernel(float4* __restrict__ theta, const float4* __restrict__ queue,
                                                      const int32_t* __restrict__ idx, int K, float lr,
                                                      const float* __restrict__ scale,
                                                      const uint32_t* __restrict__ K_dev)
 {
-    const int i = blockIdx.x * 256 + threadIdx.x;
+    const int i = blockIdx.x * APPLY_BLOCK + threadIdx.x;
     if (i >= ROW4) return;
     if (K_dev) K = (int)*K_dev;  // the consumer of the lock-free store learns the count on the device
     float4 t = theta[i];
@@ -77,12 +81,12 @@ __global__ __launch_bounds__(256) void apply_kernel(float4* __restrict__ theta, 
 // plain drain: a lane keeps its four weights and their two accumulators in registers while the rows
 // stream past.  The quotient sqrt(E[dx^2] + eps) / sqrt(E[g^2] + eps) is formed with the hardware's
 // square root and reciprocal square root (about 1 ulp each), which keeps the kernel bandwidth bound.
-__global__ __launch_bounds__(256) void apply_adadelta_kernel(float4* __restrict__ theta, float4* __restrict__ acc_g2,
+__global__ __launch_bounds__(APPLY_BLOCK) void apply_adadelta_kernel(float4* __restrict__ theta, float4* __restrict__ acc_g2,
                                                               float4* __restrict__ acc_dx2, const float4* __restrict__ queue,
                                                               const int32_t* __restrict__ idx, int K, float lr, float rho,
                                                               float eps)
 {
-    const int i = blockIdx.x * 256 + threadIdx.x;
+    const int i = blockIdx.x * APPLY_BLOCK + threadIdx.x;
     if (i >= ROW4) return;
     float t[4], g2[4], dx2[4];
     {
@@ -119,10 +123,10 @@ __global__ __launch_bounds__(256) void apply_adadelta_kernel(float4* __restrict_
 
 // Worker-local SGD steps (elastic averaging SGD: every worker trains on its own copy of the weights):
 // block row j does ring[slot_j] -= lr * queue[q_j] for the pair (slot_j, q_j); slots are distinct.
-__global__ __launch_bounds__(256) void local_step_kernel(float4* __restrict__ ring, const float4* __restrict__ queue,
+__global__ __launch_bounds__(APPLY_BLOCK) void local_step_kernel(float4* __restrict__ ring, const float4* __restrict__ queue,
                                                           const int2* __restrict__ pairs, float lr)
 {
-    const int i = blockIdx.x * 256 + threadIdx.x;
+    const int i = blockIdx.x * APPLY_BLOCK + threadIdx.x;
     if (i >= ROW4) return;
     const int2 p = pairs[blockIdx.y];
     float4* x = ring + (size_t)p.x * ROW4 + i;
@@ -135,10 +139,10 @@ __global__ __launch_bounds__(256) void local_step_kernel(float4* __restrict__ ri
 // One synchronous elastic-averaging step (Zhang et al. 2015, Section 2): with d_k = ring[slot_k] - theta,
 // all against the old theta, ring[slot_k] -= alpha d_k and theta += alpha sum_k d_k (summed in list
 // order).  One pass: a lane keeps its four centre weights while the n local copies stream through.
-__global__ __launch_bounds__(256) void elastic_average_kernel(float4* __restrict__ theta, float4* __restrict__ ring,
+__global__ __launch_bounds__(APPLY_BLOCK) void elastic_average_kernel(float4* __restrict__ theta, float4* __restrict__ ring,
                                                                const int32_t* __restrict__ slots, int n, float alpha)
 {
-    const int i = blockIdx.x * 256 + threadIdx.x;
+    const int i = blockIdx.x * APPLY_BLOCK + threadIdx.x;
     if (i >= ROW4) return;
     const float4 c = theta[i];
     float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -207,7 +211,7 @@ hipError_t launch_apply(float* theta, const float* queue, const int32_t* idx_dev
                         hipStream_t s, Profiler& prof, const uint32_t* K_dev)
 {
     if (K <= 0) return hipSuccess;
-    dim3 grid((ROW4 + 255) / 256), block(256);
+    dim3 grid((ROW4 + APPLY_BLOCK - 1) / APPLY_BLOCK), block(APPLY_BLOCK);
     prof.begin(mode == 0 ? K_APPLY_SUM : K_APPLY_SEQ, s);
     if (mode == 0)
         hipLaunchKernelGGL((apply_kernel<0, false>), grid, block, 0, s, (float4*)theta, (const float4*)queue, idx_dev, K, lr,
@@ -227,7 +231,7 @@ hipError_t launch_apply_clipped(float* theta, const float* queue, const int32_t*
     hipLaunchKernelGGL(grad_sqnorm_kernel, dim3(NORM_SLICES, K), dim3(256), 0, s, (const float4*)queue, idx_dev, partial_dev);
     prof.end(s);
     hipLaunchKernelGGL(clip_scale_kernel, dim3((K + 255) / 256), dim3(256), 0, s, partial_dev, scale_dev, K, clip);
-    dim3 grid((ROW4 + 255) / 256), block(256);
+    dim3 grid((ROW4 + APPLY_BLOCK - 1) / APPLY_BLOCK), block(APPLY_BLOCK);
     prof.begin(mode == 0 ? K_APPLY_SUM_CLIP : K_APPLY_SEQ_CLIP, s);
     if (mode == 0)
         hipLaunchKernelGGL((apply_kernel<0, true>), grid, block, 0, s, (float4*)theta, (const float4*)queue, idx_dev, K, lr,
@@ -244,7 +248,7 @@ hipError_t launch_apply_adadelta(float* theta, float* acc_g2, float* acc_dx2, co
 {
     if (K <= 0) return hipSuccess;
     prof.begin(K_APPLY_ADADELTA, s);
-    hipLaunchKernelGGL(apply_adadelta_kernel, dim3((ROW4 + 255) / 256), dim3(256), 0, s, (float4*)theta, (float4*)acc_g2,
+    hipLaunchKernelGGL(apply_adadelta_kernel, dim3((ROW4 + APPLY_BLOCK - 1) / APPLY_BLOCK), dim3(APPLY_BLOCK), 0, s, (float4*)theta, (float4*)acc_g2,
                        (float4*)acc_dx2, (const float4*)queue, idx_dev, K, lr, rho, eps);
     prof.end(s);
     return hipGetLastError();
@@ -255,7 +259,7 @@ hipError_t launch_local_steps(float* ring, const float* queue, const int32_t* pa
 {
     if (n <= 0) return hipSuccess;
     prof.begin(K_LOCAL_STEP, s);
-    hipLaunchKernelGGL(local_step_kernel, dim3((ROW4 + 255) / 256, n), dim3(256), 0, s, (float4*)ring, (const float4*)queue,
+    hipLaunchKernelGGL(local_step_kernel, dim3((ROW4 + APPLY_BLOCK - 1) / APPLY_BLOCK, n), dim3(APPLY_BLOCK), 0, s, (float4*)ring, (const float4*)queue,
                        (const int2*)pairs_dev, lr);
     prof.end(s);
     return hipGetLastError();
@@ -266,7 +270,7 @@ hipError_t launch_elastic_average(float* theta, float* ring, const int32_t* slot
 {
     if (n <= 0) return hipSuccess;
     prof.begin(K_ELASTIC, s);
-    hipLaunchKernelGGL(elastic_average_kernel, dim3((ROW4 + 255) / 256), dim3(256), 0, s, (float4*)theta, (float4*)ring,
+    hipLaunchKernelGGL(elastic_average_kernel, dim3((ROW4 + APPLY_BLOCK - 1) / APPLY_BLOCK), dim3(APPLY_BLOCK), 0, s, (float4*)theta, (float4*)ring,
                        slots_dev, n, alpha);
     prof.end(s);
     return hipGetLastError();
