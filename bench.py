@@ -51,8 +51,9 @@ MEASURED_HBM_BYTES = {
     "gemm_f32_mfma<Fc1DxEpi>": (1088.2 + 407.1 + 136.6 + 8.3) * MIB,
     "conv2_dw_kernel": (1274.1 + 145.0) * MIB, "conv2_dx_kernel": (883.0 + 5.0) * MIB,
     "grad_reduce_kernel": (194.8 + 10.2) * MIB, "apply_kernel<0>": (3180.1 + 3.1) * MIB,
-    "apply_kernel<1>": (3180.1 + 3.1) * MIB, "grad_sqnorm_kernel": (3215.8 + 1.0) * MIB,
-    "apply_kernel<1, clip>": (3180.1 + 3.1) * MIB,
+    "apply_kernel<1>": (3180.1 + 3.1) * MIB, "grad_sqnorm_kernel": (3215.3 + 1.0) * MIB,
+    "apply_kernel<1, clip>": (3180.1 + 3.1) * MIB, "apply_adadelta_kernel": (3186.3 + 9.3) * MIB,
+    "elastic_average_kernel": (797.4 + 797.4) * MIB,
 }
 
 
@@ -254,7 +255,8 @@ def main():
         if n:
             ach = algo / (ms / n * 1e-3) / 1e9
             mit.append({"kernel": name, "avg_ms": ms / n, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBPS,
-                        "unit": "GB/s", "frac": ach / PEAK_HBM_GBPS, "algorithmic_bytes": algo})
+                        "unit": "GB/s", "frac": ach / PEAK_HBM_GBPS, "algorithmic_bytes": algo,
+                        "traffic": MEASURED_HBM_BYTES.get(name)})
     out["drain_mitigated"] = mit
     ms, n = prof_async.get("apply_kernel<1>", (0.0, 0))
     if n:
@@ -267,7 +269,7 @@ def main():
         ach = algo / (ms / n * 1e-3) / 1e9
         out["elastic_average"] = {"kernel": "elastic_average_kernel", "local_copies": W, "avg_ms": ms / n, "bound": "hbm",
                                   "achieved": ach, "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBPS,
-                                  "algorithmic_bytes": algo}
+                                  "algorithmic_bytes": algo, "traffic": MEASURED_HBM_BYTES.get("elastic_average_kernel")}
     out["lockfree_store"] = {
         "schedule": f"{ROUNDS} x (append W={W} on the worker stream; SEQ server step over the 256 new rows on the server "
                     "stream) -> publish into the other ring slot; same updates in the same order as the ordered SEQ drain",
