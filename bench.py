@@ -44,7 +44,7 @@ APPLY_KERNELS = ("apply_kernel<0>", "apply_kernel<1>")
 # that changes afterwards must be set to None here until its counters are taken again.
 MIB = 1 << 20
 MEASURED_HBM_BYTES = {
-    "conv1_fwd_kernel": (200.2 + 980.0) * MIB, "conv2_fwd_kernel": (785.2 + 494.6) * MIB,
+    "conv1_fwd_kernel": (200.2 + 981.7) * MIB, "conv2_fwd_kernel": (785.2 + 494.6) * MIB,
     "gemm_f32_mfma<Fc1FwdEpi>": (578.3 + 130.5) * MIB, "fc2_kernel": (129.0 + 175.1) * MIB,
     # weight / input gradient: wide-tile launch + narrow-tile launch for the feature edge
     "gemm_f32_mfma<Fc1DwEpi>": (522.1 + 768.0 + 136.1 + 16.0) * MIB,
