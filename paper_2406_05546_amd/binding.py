@@ -67,6 +67,10 @@ def load_library() -> ctypes.CDLL:
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise FileNotFoundError(f"{LIB_PATH} not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        # torch first: it brings its own copy of the HIP runtime, and the workspace and the stream come
+        # from it, so this library must bind to that same runtime instance (loading the library before
+        # torch would pull in a second runtime that does not see torch's device context)
+        import torch  # noqa: F401
         lib = ctypes.CDLL(LIB_PATH)
         vp, i32, u64, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_uint64, ctypes.c_float
         sig = {

@@ -110,3 +110,14 @@ def test_checkpoint_scenario_shape():
     x, y = synth.eval_batch(5, 0, 16)
     xw, _ = synth.minibatch(5, synth.minibatch_id(0, 0), 16)
     assert x.shape == (16, 784) and not np.array_equal(x, xw)
+
+
+def test_loading_the_library_brings_in_torch_first():
+    """The library must bind to the HIP runtime that torch ships (torch owns the device memory and the
+    stream), whatever the caller imports first."""
+    import subprocess
+    import sys
+    code = ("import sys; from paper_2406_05546_amd import binding; assert 'torch' not in sys.modules; "
+            "binding.load_library(); assert 'torch' in sys.modules; print('ok')")
+    out = subprocess.run([sys.executable, "-c", code], cwd=ROOT, capture_output=True, text=True, timeout=300)
+    assert out.returncode == 0 and out.stdout.strip().endswith("ok"), out.stderr[-2000:]
