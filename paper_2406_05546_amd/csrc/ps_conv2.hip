@@ -110,10 +110,19 @@ __global__ __launch_bounds__(256, 2) void conv2_fwd_kernel(WorkerBuffers wb, int
 {
     constexpr int CHS = CHS_FWD, P1_IMS = C1 * CHS;
     __shared__ __attribute__((aligned(16))) float tile[FWD_G * P1_IMS];  // 67,584 B
+    // pooled position of the group -> offset of its window in the planes / of its output.  On this chip
+    // fp32 MFMAs and vector-ALU instructions do not overlap, so index arithmetic inside the tile loop
+    // is paid for in matrix time: look it up.
+    __shared__ int win_off[FWD_G * P2_POS], out_off[FWD_G * P2_POS];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, q = lane >> 4, l16 = lane & 15;
     const int w = blockIdx.x / blocks_per_worker, chunk = blockIdx.x % blocks_per_worker;
     const int B = wb.B, s_begin = chunk * FWD_IPB, s_end = min(B, s_begin + FWD_IPB);
     const float* __restrict__ W2 = worker_theta(wb, w) + OFF_W2;
+    if (tid < FWD_G * P2_POS) {
+        const int img = tid / P2_POS, pos = tid % P2_POS;
+        win_off[tid] = img * P1_IMS + 2 * (pos / P2_W) * 16 + 2 * (pos % P2_W);
+        out_off[tid] = img * P2_SIZE + pos;
+    }
 
     // B operand of k-step s (tap = s/4, channels 4*(s%4) .. +3): lane (q, l16) holds W2[o][4*(s%4)+q][tap]
     float wreg[36][2];
@@ -127,6 +136,8 @@ __global__ __launch_bounds__(256, 2) void conv2_fwd_kernel(WorkerBuffers wb, int
         reinterpret_cast<float4*>(tile)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
     __syncthreads();
 
+    // this lane's part of the A operand address: channel quarter, window element
+    const float* a_lane = tile + q * CHS + ((l16 >> 1) & 1) * 16 + (l16 & 1);
     Pool1Stage<FWD_G, CHS> stage;
     stage.prefetch(wb.p1, (size_t)w * B + s_begin, min(FWD_G, s_end - s_begin), tid);
     int rot = 0;
@@ -138,9 +149,7 @@ __global__ __launch_bounds__(256, 2) void conv2_fwd_kernel(WorkerBuffers wb, int
         if (s0 + FWD_G < s_end) stage.prefetch(wb.p1, g0 + FWD_G, min(FWD_G, s_end - s0 - FWD_G), tid);
         for (int t = (wave + rot) & 3; t < FWD_G * P2_POS / 4; t += 4) {
             // A operand: lane row l16 = (pooled position 4t + l16/4, window element l16%4)
-            const int pp = 4 * t + (l16 >> 2), img = pp / P2_POS, pos = pp % P2_POS;
-            const int y = 2 * (pos / P2_W) + ((l16 >> 1) & 1), x = 2 * (pos % P2_W) + (l16 & 1);
-            const float* a = tile + img * P1_IMS + q * CHS + y * 16 + x;
+            const float* a = a_lane + win_off[4 * t + (l16 >> 2)];
             floatx4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int s = 0; s < 36; ++s) {
@@ -149,9 +158,9 @@ __global__ __launch_bounds__(256, 2) void conv2_fwd_kernel(WorkerBuffers wb, int
                 acc1 = mfma16(av, wreg[s][1], acc1);
             }
             // lane (q, l16) now holds the 2x2 window of pooled position 4t + q for channels l16, l16+16
-            const int ppo = 4 * t + q, img_o = ppo / P2_POS, pos_o = ppo % P2_POS;
-            if (img_o < valid) {
-                const size_t out = (g0 + img_o) * P2_SIZE + pos_o;
+            const int ppo = 4 * t + q;
+            if (ppo < valid * P2_POS) {
+                const size_t out = g0 * P2_SIZE + out_off[ppo];
                 int code;
                 float best = pool_first_max(acc0[0] + bias0, acc0[1] + bias0, acc0[2] + bias0, acc0[3] + bias0, code);
                 wb.p2[out + l16 * P2_POS] = fmaxf(best, 0.f);
@@ -182,6 +191,10 @@ __global__ __launch_bounds__(256, 2) void conv2_dx_kernel(WorkerBuffers wb, int 
     constexpr int CHS = CHS_DX, D2_IMS = C2 * CHS;
     __shared__ __attribute__((aligned(16))) float tile[DX_G * D2_IMS];  // 69,632 B
     __shared__ __attribute__((aligned(16))) float xs[DX_G * 900];       // zero-padded 30x30 input images
+    // position of the group -> offset in the d2 planes; pooled position -> offset of its 2x2 window in
+    // the padded input image (looked up rather than computed: see the forward kernel)
+    __shared__ int a_off[DX_G * P1_POS];
+    __shared__ __attribute__((aligned(16))) int x_off[P1_POS];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, q = lane >> 4, l16 = lane & 15;
     const int w = blockIdx.x / blocks_per_worker, chunk = blockIdx.x % blocks_per_worker;
     const int B = wb.B, s_begin = chunk * DX_IPB, s_end = min(B, s_begin + DX_IPB);
@@ -196,6 +209,11 @@ __global__ __launch_bounds__(256, 2) void conv2_dx_kernel(WorkerBuffers wb, int 
     for (int i = tid; i < DX_G * D2_IMS / 4; i += 256)
         reinterpret_cast<float4*>(tile)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int i = tid; i < DX_G * 900; i += 256) xs[i] = 0.f;
+    for (int i = tid; i < DX_G * P1_POS; i += 256) {
+        const int img = i / P1_POS, pos = i % P1_POS;
+        a_off[i] = img * D2_IMS + (pos / P1_W) * 16 + pos % P1_W;
+        if (img == 0) x_off[pos] = 2 * (pos / P1_W) * 30 + 2 * (pos % P1_W);
+    }
     __syncthreads();
 
     // input pixels of a group: DX_G * 196 float4, at most two per thread
@@ -225,6 +243,7 @@ __global__ __launch_bounds__(256, 2) void conv2_dx_kernel(WorkerBuffers wb, int 
 #pragma unroll
     for (int i = 0; i < 9; ++i) g1[i] = 0.f;
 
+    const float* a_lane = tile + q * CHS;
     D2Stage<DX_G, CHS> stage;
     stage.prefetch(wb, (size_t)w * B + s_begin, min(DX_G, s_end - s_begin), tid);
     prefetch_x((size_t)w * B + s_begin, min(DX_G, s_end - s_begin));
@@ -242,27 +261,28 @@ __global__ __launch_bounds__(256, 2) void conv2_dx_kernel(WorkerBuffers wb, int 
         for (int t = (wave + rot) & 3; t < (DX_G * P1_POS + 15) / 16; t += 4) {
             // lane (q, l16) will hold channel l16 at positions 16t + 4q .. +3 (never straddling an image);
             // fetch their pool1 window bytes (winner, gate) before the matrix work
-            const int mo = 16 * t + 4 * q, img_o = mo / P1_POS, pos_o = mo % P1_POS;
-            const bool live = mo < DX_G * P1_POS && img_o < valid;
+            static_assert(DX_G == 2, "image of a position is found with one comparison");
+            const int mo = 16 * t + 4 * q, img_o = mo >= P1_POS ? 1 : 0, pos_o = mo - img_o * P1_POS;
+            const bool live = mo < valid * P1_POS;
             uint32_t win = 0;
             if (live) win = *reinterpret_cast<const uint32_t*>(wb.am1 + (g0 + img_o) * P1_SIZE + l16 * P1_POS + pos_o);
             // A operand: lane row l16 = position 16t + l16 of the group (reads of a row beyond the group
             // are redirected to position 0 and their results dropped)
-            const int m = 16 * t + l16, mm = m < DX_G * P1_POS ? m : 0;
-            const int img = mm / P1_POS, pos = mm % P1_POS;
-            const float* a = tile + img * D2_IMS + q * CHS + (pos / P1_W) * 16 + pos % P1_W;
+            const int m = 16 * t + l16;
+            const float* a = a_lane + a_off[m < DX_G * P1_POS ? m : 0];
             floatx4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int s = 0; s < 72; ++s)
                 acc = mfma16(a[4 * (s & 7) * CHS + ((s >> 3) / 3) * 16 + (s >> 3) % 3], wreg[s], acc);
             if (live) {
                 const float* ximg = xs + img_o * 900;
+                const int4 xo = *reinterpret_cast<const int4*>(x_off + pos_o);  // pos_o is a multiple of 4
+                const int xoff[4] = {xo.x, xo.y, xo.z, xo.w};
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const uint32_t b = win >> (8 * i);
                     const float v = (b & 4u) ? acc[i] : 0.f;
-                    const int p = pos_o + i;
-                    const float* px = ximg + (2 * (p / P1_W) + ((b >> 1) & 1)) * 30 + 2 * (p % P1_W) + (b & 1);
+                    const float* px = ximg + xoff[i] + ((b >> 1) & 1) * 30 + (b & 1);
                     gb1 += v;
 #pragma unroll
                     for (int dy = 0; dy < 3; ++dy)
@@ -302,6 +322,9 @@ __global__ __launch_bounds__(256, 2) void conv2_dw_kernel(WorkerBuffers wb)
     constexpr int CHS = CHS_DW, D2_IMS = C2 * CHS, P1_IMS = C1 * CHS;
     __shared__ __attribute__((aligned(16))) float d2[D2_IMS];   // 33,024 B
     __shared__ __attribute__((aligned(16))) float p1t[P1_IMS];  // 16,512 B
+    // position -> offset inside a padded plane.  On this chip fp32 MFMAs and vector-ALU instructions do
+    // not overlap, so index arithmetic inside the MFMA loops is paid for in matrix time: look it up.
+    __shared__ int plane_off[P1_POS];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, q = lane >> 4, l16 = lane & 15;
     const int w = blockIdx.x, chunk = blockIdx.y, B = wb.B;
     const int per = (B + N_CHUNK - 1) / N_CHUNK;
@@ -316,7 +339,10 @@ __global__ __launch_bounds__(256, 2) void conv2_dw_kernel(WorkerBuffers wb)
 
     for (int i = tid; i < D2_IMS / 4; i += 256) reinterpret_cast<float4*>(d2)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int i = tid; i < P1_IMS / 4; i += 256) reinterpret_cast<float4*>(p1t)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (tid < P1_POS) plane_off[tid] = (tid / P1_W) * 16 + tid % P1_W;
     __syncthreads();
+    const float* d2_lane = d2 + l16 * CHS + 17;
+    const float* p1_lane = p1t + l16 * CHS;
 
     D2Stage<1, CHS> sd;
     Pool1Stage<1, CHS> sp;
@@ -334,12 +360,12 @@ __global__ __launch_bounds__(256, 2) void conv2_dw_kernel(WorkerBuffers wb)
             sd.prefetch(wb, g + 1, 1, tid);
             sp.prefetch(wb.p1, g + 1, 1, tid);
         }
-        for (int ks = (wave + rot) & 3; ks < P1_POS / 4; ks += 4) {
-            const int pos = 4 * ks + q, off = (pos / P1_W) * 16 + pos % P1_W;
-            const float a0 = d2[l16 * CHS + off + 17], a1 = d2[(l16 + 16) * CHS + off + 17];
+        for (int pos = 4 * ((wave + rot) & 3) + q; pos < P1_POS; pos += 16) {
+            const int off = plane_off[pos];
+            const float a0 = d2_lane[off], a1 = d2_lane[16 * CHS + off];
             sum0 += a0;
             sum1 += a1;
-            const float* b = p1t + l16 * CHS + off;
+            const float* b = p1_lane + off;
 #pragma unroll
             for (int j = 0; j < 9; ++j) {
                 const float bv = b[(j / 3) * 16 + j % 3];
