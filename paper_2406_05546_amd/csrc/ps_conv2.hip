@@ -46,16 +46,31 @@ struct Pool1Stage {
             v[k] = *reinterpret_cast<const floatx4*>(p1 + (g0 + img) * P1_SIZE + (size_t)(i4 % (P1_SIZE / 4)) * 4);
         }
     }
-    __device__ __forceinline__ void commit(float* __restrict__ tile, int tid) const
+    // Where the float4s land does not change from group to group: a table (bits 0-14 the offset of
+    // the first element, bit 15 set when the four positions run over the end of a 14-wide row after two
+    // elements) replaces that arithmetic by one 2-byte LDS read per float4.
+    static __device__ __forceinline__ void build_table(uint16_t* __restrict__ tab, int tid)
+    {
+        static_assert(COUNT * P1_IMS < (1 << 15), "offsets must fit 15 bits");
+        for (int i4 = tid; i4 < N4; i4 += 256) {
+            const int img = i4 / (P1_SIZE / 4), r = (i4 % (P1_SIZE / 4)) * 4, c = r / P1_POS, pos = r % P1_POS;
+            const int base = img * P1_IMS + c * CHS + 17 + (pos / P1_W) * 16 + pos % P1_W;  // interior starts at (1,1)
+            tab[i4] = (uint16_t)(base | (pos % P1_W == P1_W - 2 ? 0x8000 : 0));
+        }
+    }
+    __device__ __forceinline__ void commit(float* __restrict__ tile, const uint16_t* __restrict__ tab, int tid) const
     {
 #pragma unroll
         for (int k = 0; k < NV; ++k) {
             const int i4 = tid + 256 * k;
-            const int img = i4 / (P1_SIZE / 4), r = (i4 % (P1_SIZE / 4)) * 4, c = r / P1_POS, pos = r % P1_POS;
-            float* plane = tile + img * P1_IMS + c * CHS + 17;  // (1,1)
             if (256 * (k + 1) <= N4 || i4 < N4) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) plane[((pos + j) / P1_W) * 16 + (pos + j) % P1_W] = v[k][j];
+                const uint32_t e = tab[i4];
+                float* dst = tile + (e & 0x7fffu);
+                const uint32_t hop = (e >> 15) * 2;  // the next row starts 16 - 14 further on
+                dst[0] = v[k][0];
+                dst[1] = v[k][1];
+                dst[2 + hop] = v[k][2];
+                dst[3 + hop] = v[k][3];
             }
         }
     }
@@ -114,6 +129,7 @@ __global__ __launch_bounds__(256, 2) void conv2_fwd_kernel(WorkerBuffers wb, int
     // fp32 MFMAs and vector-ALU instructions do not overlap, so index arithmetic inside the tile loop
     // is paid for in matrix time: look it up.
     __shared__ int win_off[FWD_G * P2_POS], out_off[FWD_G * P2_POS];
+    __shared__ uint16_t stage_tab[Pool1Stage<FWD_G, CHS_FWD>::N4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, q = lane >> 4, l16 = lane & 15;
     const int w = blockIdx.x / blocks_per_worker, chunk = blockIdx.x % blocks_per_worker;
     const int B = wb.B, s_begin = chunk * FWD_IPB, s_end = min(B, s_begin + FWD_IPB);
@@ -123,13 +139,15 @@ __global__ __launch_bounds__(256, 2) void conv2_fwd_kernel(WorkerBuffers wb, int
         win_off[tid] = img * P1_IMS + 2 * (pos / P2_W) * 16 + 2 * (pos % P2_W);
         out_off[tid] = img * P2_SIZE + pos;
     }
+    Pool1Stage<FWD_G, CHS>::build_table(stage_tab, tid);
 
-    // B operand of k-step s (tap = s/4, channels 4*(s%4) .. +3): lane (q, l16) holds W2[o][4*(s%4)+q][tap]
+    // B operand of k-step s (channels 4*(s/9) .. +3, tap = s%9): lane (q, l16) holds W2[o][4*(s/9)+q][tap].
+    // Taps innermost: the nine A reads of a channel group then share one LDS base address.
     float wreg[36][2];
 #pragma unroll
     for (int s = 0; s < 36; ++s)
 #pragma unroll
-        for (int hf = 0; hf < 2; ++hf) wreg[s][hf] = W2[((l16 + 16 * hf) * C1 + 4 * (s & 3) + q) * 9 + (s >> 2)];
+        for (int hf = 0; hf < 2; ++hf) wreg[s][hf] = W2[((l16 + 16 * hf) * C1 + 4 * (s / 9) + q) * 9 + s % 9];
     const float bias0 = W2[C2 * C1 * 9 + l16], bias1 = W2[C2 * C1 * 9 + 16 + l16];
 
     for (int i = tid; i < FWD_G * P1_IMS / 4; i += 256)
@@ -144,7 +162,7 @@ __global__ __launch_bounds__(256, 2) void conv2_fwd_kernel(WorkerBuffers wb, int
     for (int s0 = s_begin; s0 < s_end; s0 += FWD_G, ++rot) {
         const size_t g0 = (size_t)w * B + s0;
         const int valid = min(FWD_G, s_end - s0);
-        stage.commit(tile, tid);
+        stage.commit(tile, stage_tab, tid);
         __syncthreads();
         if (s0 + FWD_G < s_end) stage.prefetch(wb.p1, g0 + FWD_G, min(FWD_G, s_end - s0 - FWD_G), tid);
         for (int t = (wave + rot) & 3; t < FWD_G * P2_POS / 4; t += 4) {
@@ -153,7 +171,7 @@ __global__ __launch_bounds__(256, 2) void conv2_fwd_kernel(WorkerBuffers wb, int
             floatx4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int s = 0; s < 36; ++s) {
-                const float av = a[4 * (s & 3) * CHS + ((s >> 2) / 3) * 16 + (s >> 2) % 3];
+                const float av = a[4 * (s / 9) * CHS + ((s % 9) / 3) * 16 + (s % 9) % 3];
                 acc0 = mfma16(av, wreg[s][0], acc0);
                 acc1 = mfma16(av, wreg[s][1], acc1);
             }
@@ -201,7 +219,8 @@ __global__ __launch_bounds__(256, 2) void conv2_dx_kernel(WorkerBuffers wb, int 
     const float* __restrict__ W2 = worker_theta(wb, w) + OFF_W2;
 
     // B operand of k-step s (flipped tap t' = s/8, output channels 4*(s%8) .. +3): lane (q, l16) holds
-    // W2[4*(s%8)+q][c = l16][8 - t']
+    // W2[4*(s%8)+q][c = l16][8 - t']  (channel groups innermost measured faster here, taps innermost in
+    // the forward kernel)
     float wreg[72];
 #pragma unroll
     for (int s = 0; s < 72; ++s) wreg[s] = W2[((4 * (s & 7) + q) * C1 + l16) * 9 + 8 - (s >> 3)];
@@ -325,6 +344,7 @@ __global__ __launch_bounds__(256, 2) void conv2_dw_kernel(WorkerBuffers wb)
     // position -> offset inside a padded plane.  On this chip fp32 MFMAs and vector-ALU instructions do
     // not overlap, so index arithmetic inside the MFMA loops is paid for in matrix time: look it up.
     __shared__ int plane_off[P1_POS];
+    __shared__ uint16_t stage_tab[Pool1Stage<1, CHS_DW>::N4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, q = lane >> 4, l16 = lane & 15;
     const int w = blockIdx.x, chunk = blockIdx.y, B = wb.B;
     const int per = (B + N_CHUNK - 1) / N_CHUNK;
@@ -340,6 +360,7 @@ __global__ __launch_bounds__(256, 2) void conv2_dw_kernel(WorkerBuffers wb)
     for (int i = tid; i < D2_IMS / 4; i += 256) reinterpret_cast<float4*>(d2)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int i = tid; i < P1_IMS / 4; i += 256) reinterpret_cast<float4*>(p1t)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
     if (tid < P1_POS) plane_off[tid] = (tid / P1_W) * 16 + tid % P1_W;
+    Pool1Stage<1, CHS>::build_table(stage_tab, tid);
     __syncthreads();
     const float* d2_lane = d2 + l16 * CHS + 17;
     const float* p1_lane = p1t + l16 * CHS;
@@ -354,7 +375,7 @@ __global__ __launch_bounds__(256, 2) void conv2_dw_kernel(WorkerBuffers wb)
     for (int s = s_begin; s < s_end; ++s, ++rot) {
         const size_t g = (size_t)w * B + s;
         sd.commit(d2, tid);
-        sp.commit(p1t, tid);
+        sp.commit(p1t, stage_tab, tid);
         __syncthreads();
         if (s + 1 < s_end) {
             sd.prefetch(wb, g + 1, 1, tid);
