@@ -66,13 +66,17 @@ def test_store_in_lockstep_with_the_oracle_over_a_wrapping_queue(ps):
             x, y = synth.minibatches(DATA_SEED, mbs, B)
             xd, yd = _dev(x, y)
             say(f"store lockstep: round {r} append on slot {slot}")
-            ps.worker_grads_append(ctx, workers, [slot] * W, mbs, xd, yd)
+            import torch
+            loss = torch.zeros(W, device="cuda")
+            ps.worker_grads_append(ctx, workers, [slot] * W, mbs, xd, yd, loss)
             st = ps.ps_store_state(ctx)
             assert (st["claimed"], st["published"], st["consumed"]) == (W * (r + 1), W * (r + 1), W * r)
             ref = o.worker_grads_batched(workers, [slot] * W, mbs, x, y)
+            losses = loss.cpu().numpy()
             for i in range(W):
                 g, wk, ver, mb = ps.ps_store_entry(ctx, W * r + i)
                 assert (wk, ver, mb) == (workers[i], ref[i].version, mbs[i])
+                assert abs(losses[i] - ref[i].loss) <= 2e-5 * abs(ref[i].loss)
                 if not parity.is_close(g, ref[i].grad, parity.GRAD_TOL):
                     res = parity.check_worker(ps, ctx, i, -1, o.ring[slot], x[i], y[i], mbs[i], DROP_SEED, P_DROP,
                                               f"round {r} worker {i}", grad=g)
@@ -82,6 +86,15 @@ def test_store_in_lockstep_with_the_oracle_over_a_wrapping_queue(ps):
             expected_steps.append((W * r, W, mode, o.version))
             ps.ps_store_publish(ctx, 1 - slot)
             o.snapshot_weights(1 - slot)
+            if r == 2:
+                # evaluation in the middle of a store session waits for both streams and sees the step just enqueued
+                ex, ey = synth.eval_batch(DATA_SEED, r, 2 * B)
+                exd, eyd = _dev(ex, ey)
+                gl, ga, gp = ps.ps_evaluate(ctx, -1, exd, eyd)
+                ol, oa, op, oz = orc.evaluate(orc.Dims(), o.theta, ex, ey)
+                zs = np.sort(oz, axis=1)
+                clear = (zs[:, -1] - zs[:, -2]) > 1e-4
+                assert abs(gl - ol) <= 2e-5 * abs(ol) and np.array_equal(gp[clear], op[clear])
             parity.assert_close(ps.ps_get_weights(ctx), o.theta, parity.WEIGHT_TOL, f"weights after round {r}")
             parity.assert_close(ps.ps_get_weights(ctx, 1 - slot), o.ring[1 - slot], parity.WEIGHT_TOL, "published slot")
             st = ps.ps_store_state(ctx)
