@@ -17,10 +17,18 @@ constexpr int APPLY_BLOCK = 64;
 
 __device__ __forceinline__ float4 ld_stream(const float4* p)
 {
-    // The queue is read once and never again: keep it out of the caches' way.
+    // For data a kernel reads once and never again (queue rows, streamed weight copies): keep it out
+    // of the caches' way.
     typedef float v4f __attribute__((ext_vector_type(4)));
     v4f v = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p));
     return make_float4(v.x, v.y, v.z, v.w);
+}
+
+__device__ __forceinline__ void st_stream(float4* p, float4 x)
+{
+    typedef float v4f __attribute__((ext_vector_type(4)));
+    const v4f v = {x.x, x.y, x.z, x.w};
+    __builtin_nontemporal_store(v, reinterpret_cast<v4f*>(p));
 }
 
 // SCALED: gradient k is multiplied by scale[k] first (norm clipping of stale gradients).
@@ -131,14 +139,18 @@ __global__ __launch_bounds__(APPLY_BLOCK) void local_step_kernel(float4* __restr
     const int2 p = pairs[blockIdx.y];
     float4* x = ring + (size_t)p.x * ROW4 + i;
     const float4 g = ld_stream(queue + (size_t)p.y * ROW4 + i);
-    float4 t = *x;
+    float4 t = ld_stream(x);
     t.x = fmaf(-lr, g.x, t.x); t.y = fmaf(-lr, g.y, t.y); t.z = fmaf(-lr, g.z, t.z); t.w = fmaf(-lr, g.w, t.w);
-    *x = t;
+    st_stream(x, t);
 }
 
 // One synchronous elastic-averaging step (Zhang et al. 2015, Section 2): with d_k = ring[slot_k] - theta,
 // all against the old theta, ring[slot_k] -= alpha d_k and theta += alpha sum_k d_k (summed in list
 // order).  One pass: a lane keeps its four centre weights while the n local copies stream through.
+// Unlike the read-only streams above this one writes as much as it reads, and it runs fastest with
+// one row per iteration and cache-bypassing loads and stores (6.0 TB/s in a timing probe of this
+// access pattern, against 5.0 TB/s with eight loads batched before eight stores and 5.3 TB/s for
+// the runtime's device-to-device copy of the same bytes).
 __global__ __launch_bounds__(APPLY_BLOCK) void elastic_average_kernel(float4* __restrict__ theta, float4* __restrict__ ring,
                                                                const int32_t* __restrict__ slots, int n, float alpha)
 {
@@ -146,25 +158,13 @@ __global__ __launch_bounds__(APPLY_BLOCK) void elastic_average_kernel(float4* __
     if (i >= ROW4) return;
     const float4 c = theta[i];
     float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-    int k = 0;
-    for (; k + UNROLL <= n; k += UNROLL) {
-        float4 x[UNROLL];
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) x[u] = ring[(size_t)slots[k + u] * ROW4 + i];
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            const float4 d = make_float4(x[u].x - c.x, x[u].y - c.y, x[u].z - c.z, x[u].w - c.w);
-            s.x += d.x; s.y += d.y; s.z += d.z; s.w += d.w;
-            ring[(size_t)slots[k + u] * ROW4 + i] =
-                make_float4(fmaf(-alpha, d.x, x[u].x), fmaf(-alpha, d.y, x[u].y), fmaf(-alpha, d.z, x[u].z), fmaf(-alpha, d.w, x[u].w));
-        }
-    }
-    for (; k < n; ++k) {
+#pragma unroll 1
+    for (int k = 0; k < n; ++k) {
         float4* px = ring + (size_t)slots[k] * ROW4 + i;
-        const float4 x = *px;
+        const float4 x = ld_stream(px);
         const float4 d = make_float4(x.x - c.x, x.y - c.y, x.z - c.z, x.w - c.w);
         s.x += d.x; s.y += d.y; s.z += d.z; s.w += d.w;
-        *px = make_float4(fmaf(-alpha, d.x, x.x), fmaf(-alpha, d.y, x.y), fmaf(-alpha, d.z, x.z), fmaf(-alpha, d.w, x.w));
+        st_stream(px, make_float4(fmaf(-alpha, d.x, x.x), fmaf(-alpha, d.y, x.y), fmaf(-alpha, d.z, x.z), fmaf(-alpha, d.w, x.w)));
     }
     theta[i] = make_float4(fmaf(alpha, s.x, c.x), fmaf(alpha, s.y, c.y), fmaf(alpha, s.z, c.z), fmaf(alpha, s.w, c.w));
 }
