@@ -41,7 +41,7 @@ __device__ __forceinline__ float wave_sum(float v)
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
-__global__ __launch_bounds__(256) void fc2_kernel(WorkerBuffers wb)
+__global__ __launch_bounds__(256, 2) void fc2_kernel(WorkerBuffers wb)
 {
     const int lane = threadIdx.x & 63, w = blockIdx.x, B = wb.B;
     const int nsub = 4 * gridDim.y, sub = 4 * blockIdx.y + (threadIdx.x >> 6);
