@@ -16,7 +16,9 @@ struct Fc1FwdEpi {
     WorkerBuffers wb;
     __device__ const float* a_ptr(int z) const { return worker_theta(wb, z) + OFF_W3; }
     __device__ const float* b_ptr(int z) const { return wb.p2 + (size_t)z * wb.B * P2_SIZE; }
-    __device__ void operator()(int z, int m, int n, float4 acc) const
+    struct Pre {};
+    __device__ Pre prefetch(int, int, int) const { return Pre{}; }
+    __device__ void operator()(int z, int m, int n, float4 acc, Pre) const
     {
         const float4 b = *reinterpret_cast<const float4*>(worker_theta(wb, z) + OFF_B3 + m);
         const WorkerMeta mt = wb.meta[z];
@@ -32,21 +34,26 @@ struct Fc1FwdEpi {
 };
 
 // d pool2 = d3 . W3, zeroed where the pooled activation is zero (ReLU gate of conv2).
-// Rows m are pool2 features, columns n samples, contraction over the 512 units.
+// Rows m are pool2 features, columns n samples, contraction over the 512 units.  The gate is bit 2 of
+// the pool2 window bytes (winner > 0, which is the same as pooled activation > 0): four bytes per
+// epilogue call, fetched before the contraction starts.
 struct Fc1DxEpi {
     WorkerBuffers wb;
     __device__ const float* a_ptr(int z) const { return worker_theta(wb, z) + OFF_W3; }
     __device__ const float* b_ptr(int z) const { return wb.d3 + (size_t)z * wb.B * FC1; }
-    __device__ void operator()(int z, int m, int n, float4 acc) const
+    typedef uint32_t Pre;
+    __device__ Pre prefetch(int z, int m, int n) const
     {
-        const size_t at = ((size_t)z * wb.B + n) * P2_SIZE + m;
-        const float4 a = *reinterpret_cast<const float4*>(wb.p2 + at);
+        return *reinterpret_cast<const uint32_t*>(wb.am2 + ((size_t)z * wb.B + n) * P2_SIZE + m);  // m % 4 == 0
+    }
+    __device__ void operator()(int z, int m, int n, float4 acc, Pre gate) const
+    {
         float4 o;
-        o.x = a.x > 0.f ? acc.x : 0.f;
-        o.y = a.y > 0.f ? acc.y : 0.f;
-        o.z = a.z > 0.f ? acc.z : 0.f;
-        o.w = a.w > 0.f ? acc.w : 0.f;
-        *reinterpret_cast<float4*>(wb.dp2g + at) = o;
+        o.x = (gate & 0x00000004u) ? acc.x : 0.f;
+        o.y = (gate & 0x00000400u) ? acc.y : 0.f;
+        o.z = (gate & 0x00040000u) ? acc.z : 0.f;
+        o.w = (gate & 0x04000000u) ? acc.w : 0.f;
+        *reinterpret_cast<float4*>(wb.dp2g + ((size_t)z * wb.B + n) * P2_SIZE + m) = o;
     }
 };
 
@@ -56,7 +63,9 @@ struct Fc1DwEpi {
     WorkerBuffers wb;
     __device__ const float* a_ptr(int z) const { return wb.d3 + (size_t)z * wb.B * FC1; }
     __device__ const float* b_ptr(int z) const { return wb.p2 + (size_t)z * wb.B * P2_SIZE; }
-    __device__ void operator()(int z, int m, int n, float4 acc) const
+    struct Pre {};
+    __device__ Pre prefetch(int, int, int) const { return Pre{}; }
+    __device__ void operator()(int z, int m, int n, float4 acc, Pre) const
     {
         float* g = worker_grad(wb, z) + OFF_W3 + (size_t)m * P2_SIZE + n;
         g[0] = acc.x;

@@ -19,7 +19,9 @@
 // the batch index is then fetched from HBM once and re-used out of that L2.
 //
 // The epilogue functor receives four consecutive rows m..m+3 of one column n:
-//   epi(z, m, n, float4 acc)   with m % 4 == 0.
+//   epi(z, m, n, float4 acc, pre)   with m % 4 == 0,
+// where pre = epi.prefetch(z, m, n) was fetched before the K loop (type Epi::Pre; an empty struct if the
+// epilogue needs nothing from memory), so that its latency hides under the whole contraction.
 #pragma once
 #include "ps_common.h"
 
@@ -131,12 +133,20 @@ __global__ __launch_bounds__(256, MINW) void gemm_f32_mfma(GemmShape sh, Epi epi
     const float* __restrict__ B = epi.b_ptr(z);
 
     floatx16 acc[TM][TN];
+    typename Epi::Pre pre[TM][TN][4];
 #pragma unroll
     for (int a = 0; a < TM; ++a)
 #pragma unroll
-        for (int b = 0; b < TN; ++b)
+        for (int b = 0; b < TN; ++b) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+            const int n = n0 + (wn * TN + b) * 32 + l32;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int m = m0 + (wm * TM + a) * 32 + 8 * g + 4 * h;
+                pre[a][b][g] = (m < sh.M && n < sh.N) ? epi.prefetch(z, m, n) : typename Epi::Pre{};
+            }
+        }
 
     // Three-deep pipeline: while the matrix cores consume stage kt out of one LDS buffer, stage kt+1
     // (loaded from HBM/L2 during the previous iteration) is written into the other buffer half way
@@ -201,7 +211,8 @@ __global__ __launch_bounds__(256, MINW) void gemm_f32_mfma(GemmShape sh, Epi epi
                 const int m = m0 + (wm * TM + a) * 32 + 8 * g + 4 * h;
                 if (m < sh.M && n < sh.N)
                     epi(z, m, n,
-                        make_float4(acc[a][b][4 * g], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2], acc[a][b][4 * g + 3]));
+                        make_float4(acc[a][b][4 * g], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2], acc[a][b][4 * g + 3]),
+                        pre[a][b][g]);
             }
         }
 }
