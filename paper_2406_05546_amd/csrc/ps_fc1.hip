@@ -78,33 +78,31 @@ struct Fc1DwEpi {
 }  // namespace
 
 // All three use 128 x 128 block tiles (four wavefronts of 64 x 64), K stepped 16 at a time.  The 1568
-// features are 12 such tiles plus 32: that edge gets its own launch with 32-wide tiles (four
-// wavefronts of 32 x 32 side by side) instead of a thirteenth wide tile that would be three quarters
-// empty.
+// features are 12 such tiles plus 32: that edge is covered with 32-wide tiles (four wavefronts of
+// 32 x 32 side by side) instead of a thirteenth wide tile that would be three quarters empty, by extra
+// blocks of the same launch that run next to the last wide tiles.
 constexpr int FEAT_WIDE = P2_SIZE / 128 * 128;  // 1536
 
 // forward: rows = 512 units (W3, k-contiguous), columns = the worker's samples (pool2, k-contiguous)
 void launch_fc1_fwd(const WorkerBuffers& wb, hipStream_t s)
 {
-    gemm_launch<true, true, 2, 2, 2, 2, 16, 1>(FC1, wb.B, P2_SIZE, P2_SIZE, P2_SIZE, wb.n, Fc1FwdEpi{wb}, s);
+    gemm_launch<GemmCfg<true, true, 2, 2, 2, 2, 16>, 1>(FC1, wb.B, P2_SIZE, P2_SIZE, P2_SIZE, wb.n, Fc1FwdEpi{wb}, s);
 }
 
 // weight gradient: rows = 512 units (d3, row-contiguous), columns = 1568 features (pool2, row-contiguous),
 // contraction over the worker's samples
 void launch_fc1_dw(const WorkerBuffers& wb, hipStream_t s)
 {
-    const Fc1DwEpi epi{wb};
-    gemm_launch_range<false, false, 2, 2, 2, 2, 16, 1>(FC1, P2_SIZE, wb.B, FC1, P2_SIZE, wb.n, 0, FC1, 0, FEAT_WIDE, epi, s);
-    gemm_launch_range<false, false, 1, 1, 4, 1, 16, 1>(FC1, P2_SIZE, wb.B, FC1, P2_SIZE, wb.n, 0, FC1, FEAT_WIDE, P2_SIZE, epi, s);
+    gemm_launch_edge<GemmCfg<false, false, 2, 2, 2, 2, 16>, GemmCfg<false, false, 1, 1, 4, 1, 16>, 1>(
+        FC1, P2_SIZE, wb.B, FC1, P2_SIZE, wb.n, FC1, FEAT_WIDE, Fc1DwEpi{wb}, s);
 }
 
 // input gradient: rows = 1568 features (W3, row-contiguous), columns = samples (d3, k-contiguous),
 // contraction over the 512 units
 void launch_fc1_dx(const WorkerBuffers& wb, hipStream_t s)
 {
-    const Fc1DxEpi epi{wb};
-    gemm_launch_range<false, true, 2, 2, 2, 2, 16, 1>(P2_SIZE, wb.B, FC1, P2_SIZE, FC1, wb.n, 0, FEAT_WIDE, 0, wb.B, epi, s);
-    gemm_launch_range<false, true, 1, 1, 1, 4, 16, 1>(P2_SIZE, wb.B, FC1, P2_SIZE, FC1, wb.n, FEAT_WIDE, P2_SIZE, 0, wb.B, epi, s);
+    gemm_launch_edge<GemmCfg<false, true, 2, 2, 2, 2, 16>, GemmCfg<false, true, 1, 1, 1, 4, 16>, 1>(
+        P2_SIZE, wb.B, FC1, P2_SIZE, FC1, wb.n, FEAT_WIDE, wb.B, Fc1DxEpi{wb}, s);
 }
 
 }  // namespace ps

@@ -110,14 +110,29 @@ struct GemmOperand {
     }
 };
 
-template <bool A_KC, bool B_KC, int TM, int TN, int WM, int WN, int KS, bool RAGGED, int MINW, class Epi>
-__global__ __launch_bounds__(256, MINW) void gemm_f32_mfma(GemmShape sh, Epi epi)
-{
+// Tile configuration of one launch.
+template <bool A_KC_, bool B_KC_, int TM_, int TN_, int WM_, int WN_, int KS_>
+struct GemmCfg {
+    static constexpr bool A_KC = A_KC_, B_KC = B_KC_;
+    static constexpr int TM = TM_, TN = TN_, WM = WM_, WN = WN_, KS = KS_;
+    static constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
     static_assert(WM * WN == 4, "four wavefronts per block");
-    constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
+    template <bool RAGGED>
+    static constexpr int lds_floats()  // one of the two stage buffers
+    {
+        return GemmOperand<BM, KS, A_KC, RAGGED>::FLOATS + GemmOperand<BN, KS, B_KC, RAGGED>::FLOATS;
+    }
+};
+
+// One block's tile: `block` of `sh.gx * sh.gy * sh.gz` (rounded up to the XCD count), stage buffers in lds.
+template <class Cfg, bool RAGGED, class Epi>
+__device__ __forceinline__ void gemm_block(const GemmShape& sh, const Epi& epi, int block, float* __restrict__ lds)
+{
+    constexpr bool A_KC = Cfg::A_KC, B_KC = Cfg::B_KC;
+    constexpr int TM = Cfg::TM, TN = Cfg::TN, WM = Cfg::WM, WN = Cfg::WN, KS = Cfg::KS, BM = Cfg::BM, BN = Cfg::BN;
     using OpA = GemmOperand<BM, KS, A_KC, RAGGED>;
     using OpB = GemmOperand<BN, KS, B_KC, RAGGED>;
-    __shared__ __attribute__((aligned(16))) float lds[2][OpA::FLOATS + OpB::FLOATS];
+    constexpr int STAGE = OpA::FLOATS + OpB::FLOATS;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -126,7 +141,7 @@ __global__ __launch_bounds__(256, MINW) void gemm_f32_mfma(GemmShape sh, Epi epi
 
     // XCD-aware numbering: XCD x (= linear id mod 8) walks a contiguous range of (z, y, x) triples.
     const int total = sh.gx * sh.gy * sh.gz, per_xcd = (total + GEMM_XCDS - 1) / GEMM_XCDS;
-    const int v = (blockIdx.x % GEMM_XCDS) * per_xcd + blockIdx.x / GEMM_XCDS;
+    const int v = (block % GEMM_XCDS) * per_xcd + block / GEMM_XCDS;
     if (v >= total) return;
     const int m0 = sh.m_base + (v % sh.gx) * BM, n0 = sh.n_base + (v / sh.gx % sh.gy) * BN, z = v / (sh.gx * sh.gy);
     const float* __restrict__ A = epi.a_ptr(z);
@@ -163,15 +178,16 @@ __global__ __launch_bounds__(256, MINW) void gemm_f32_mfma(GemmShape sh, Epi epi
         opb.load(0, rb0);
         opa.load(min(1, nk - 1), ra);
         opb.load(min(1, nk - 1), rb);
-        OpA::store(lds[0], tid, ra0);
-        OpB::store(lds[0] + OpA::FLOATS, tid, rb0);
+        OpA::store(lds, tid, ra0);
+        OpB::store(lds + OpA::FLOATS, tid, rb0);
     }
     __syncthreads();
 
     for (int kt = 0; kt < nk; ++kt) {
         const int cur = kt & 1;
-        const float* ta = lds[cur];
-        const float* tb = lds[cur] + OpA::FLOATS;
+        const float* ta = lds + cur * STAGE;
+        const float* tb = ta + OpA::FLOATS;
+        float* na = lds + (cur ^ 1) * STAGE;
 #pragma unroll
         for (int j = 0; j < KS / 8; ++j) {
             floatx4v fa[TM], fb[TN];
@@ -191,8 +207,8 @@ __global__ __launch_bounds__(256, MINW) void gemm_f32_mfma(GemmShape sh, Epi epi
             if (j == KS / 16 - 1) {
                 // unconditional on purpose (straight-line code schedules under the MFMAs): past the
                 // end the last stage is simply loaded and stored again where nobody reads it
-                OpA::store(lds[cur ^ 1], tid, ra);
-                OpB::store(lds[cur ^ 1] + OpA::FLOATS, tid, rb);
+                OpA::store(na, tid, ra);
+                OpB::store(na + OpA::FLOATS, tid, rb);
                 opa.load(min(kt + 2, nk - 1), ra);
                 opb.load(min(kt + 2, nk - 1), rb);
             }
@@ -217,31 +233,69 @@ __global__ __launch_bounds__(256, MINW) void gemm_f32_mfma(GemmShape sh, Epi epi
         }
 }
 
-// Launches, per batch index, the tiles that cover rows [m_begin, m_end) and columns [n_begin, n_end)
-// of C (begins must be multiples of the instance's block tile unless zero) over a 1-D grid padded to
-// a multiple of the XCD count.  Covering C with a wide-tile launch plus a narrow-tile launch for the
-// ragged edge avoids running a mostly empty wide tile.
-template <bool A_KC, bool B_KC, int TM, int TN, int WM, int WN, int KS, int MINW, class Epi>
-void gemm_launch_range(int M, int N, int K, int lda, int ldb, int batch, int m_begin, int m_end, int n_begin, int n_end,
-                       const Epi& epi, hipStream_t s)
+constexpr int gemm_grid(const GemmShape& sh) { return (sh.gx * sh.gy * sh.gz + GEMM_XCDS - 1) / GEMM_XCDS * GEMM_XCDS; }
+
+template <class Cfg, bool RAGGED, int MINW, class Epi>
+__global__ __launch_bounds__(256, MINW) void gemm_f32_mfma(GemmShape sh, Epi epi)
 {
-    constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
-    if (m_end <= m_begin || n_end <= n_begin || batch <= 0) return;
-    GemmShape sh{M, N, K, lda, ldb, (m_end - m_begin + BM - 1) / BM, (n_end - n_begin + BN - 1) / BN, batch, m_begin, n_begin};
-    const int total = sh.gx * sh.gy * sh.gz;
-    const int grid = (total + GEMM_XCDS - 1) / GEMM_XCDS * GEMM_XCDS;
-    if (K % KS == 0)
-        hipLaunchKernelGGL((gemm_f32_mfma<A_KC, B_KC, TM, TN, WM, WN, KS, false, MINW, Epi>), dim3(grid), dim3(256), 0, s,
-                           sh, epi);
-    else
-        hipLaunchKernelGGL((gemm_f32_mfma<A_KC, B_KC, TM, TN, WM, WN, KS, true, MINW, Epi>), dim3(grid), dim3(256), 0, s,
-                           sh, epi);
+    __shared__ __attribute__((aligned(16))) float lds[2 * Cfg::template lds_floats<RAGGED>()];
+    gemm_block<Cfg, RAGGED>(sh, epi, blockIdx.x, lds);
 }
 
-template <bool A_KC, bool B_KC, int TM, int TN, int WM, int WN, int KS, int MINW, class Epi>
+// Two tile shapes in one launch: the first `main_blocks` blocks cover the main part of C with Main tiles,
+// the rest cover an edge strip with Edge tiles.  The edge blocks are dispatched last and run next to the
+// last main blocks instead of as a launch of their own behind them.
+template <class Main, class Edge, bool RAGGED, int MINW, class Epi>
+__global__ __launch_bounds__(256, MINW) void gemm_f32_mfma_edge(GemmShape sh_main, GemmShape sh_edge, int main_blocks, Epi epi)
+{
+    constexpr int LDS = Main::template lds_floats<RAGGED>() > Edge::template lds_floats<RAGGED>()
+                            ? Main::template lds_floats<RAGGED>()
+                            : Edge::template lds_floats<RAGGED>();
+    __shared__ __attribute__((aligned(16))) float lds[2 * LDS];
+    if ((int)blockIdx.x < main_blocks)  // uniform over the block
+        gemm_block<Main, RAGGED>(sh_main, epi, blockIdx.x, lds);
+    else
+        gemm_block<Edge, RAGGED>(sh_edge, epi, blockIdx.x - main_blocks, lds);
+}
+
+template <class Cfg>
+GemmShape gemm_shape(int M, int N, int K, int lda, int ldb, int batch, int m_begin, int m_end, int n_begin, int n_end)
+{
+    return GemmShape{M, N, K, lda, ldb, (m_end - m_begin + Cfg::BM - 1) / Cfg::BM, (n_end - n_begin + Cfg::BN - 1) / Cfg::BN,
+                     batch, m_begin, n_begin};
+}
+
+// One problem per batch index, all of C covered with Cfg tiles over a 1-D grid padded to a multiple of
+// the XCD count.
+template <class Cfg, int MINW, class Epi>
 void gemm_launch(int M, int N, int K, int lda, int ldb, int batch, const Epi& epi, hipStream_t s)
 {
-    gemm_launch_range<A_KC, B_KC, TM, TN, WM, WN, KS, MINW>(M, N, K, lda, ldb, batch, 0, M, 0, N, epi, s);
+    if (M <= 0 || N <= 0 || batch <= 0) return;
+    const GemmShape sh = gemm_shape<Cfg>(M, N, K, lda, ldb, batch, 0, M, 0, N);
+    if (K % Cfg::KS == 0)
+        hipLaunchKernelGGL((gemm_f32_mfma<Cfg, false, MINW, Epi>), dim3(gemm_grid(sh)), dim3(256), 0, s, sh, epi);
+    else
+        hipLaunchKernelGGL((gemm_f32_mfma<Cfg, true, MINW, Epi>), dim3(gemm_grid(sh)), dim3(256), 0, s, sh, epi);
+}
+
+// Rows [0, m_split) x columns [0, n_split) of C with Main tiles and the rest with Edge tiles, where exactly
+// one of the splits is inside C (the other equals M or N) and is a multiple of Main's tile: covering a
+// ragged edge with narrow tiles avoids a mostly empty wide tile.
+template <class Main, class Edge, int MINW, class Epi>
+void gemm_launch_edge(int M, int N, int K, int lda, int ldb, int batch, int m_split, int n_split, const Epi& epi, hipStream_t s)
+{
+    static_assert(Main::KS == Edge::KS, "one K step for both tile shapes");
+    if (M <= 0 || N <= 0 || batch <= 0) return;
+    const GemmShape sh_main = gemm_shape<Main>(M, N, K, lda, ldb, batch, 0, m_split, 0, n_split);
+    const GemmShape sh_edge = m_split < M ? gemm_shape<Edge>(M, N, K, lda, ldb, batch, m_split, M, 0, N)
+                                          : gemm_shape<Edge>(M, N, K, lda, ldb, batch, 0, M, n_split, N);
+    const int main_blocks = gemm_grid(sh_main), grid = main_blocks + gemm_grid(sh_edge);
+    if (K % Main::KS == 0)
+        hipLaunchKernelGGL((gemm_f32_mfma_edge<Main, Edge, false, MINW, Epi>), dim3(grid), dim3(256), 0, s, sh_main, sh_edge,
+                           main_blocks, epi);
+    else
+        hipLaunchKernelGGL((gemm_f32_mfma_edge<Main, Edge, true, MINW, Epi>), dim3(grid), dim3(256), 0, s, sh_main, sh_edge,
+                           main_blocks, epi);
 }
 
 }  // namespace ps
