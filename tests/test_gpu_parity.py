@@ -79,6 +79,34 @@ def test_one_call_decisions_gradients_and_stale_slots(ps):
         ps.ps_destroy(ctx)
 
 
+# Shapes around the kernels' tile edges: one image, fewer images than an MFMA tile has rows, one more than
+# a conv group (2, 4) or a GEMM tile (128, 256) holds, many workers with tiny batches.
+@pytest.mark.parametrize("n,B", [(1, 1), (2, 3), (3, 15), (2, 17), (2, 33), (2, 65), (1, 129), (1, 257), (13, 3), (40, 1)])
+def test_ragged_shapes_against_the_oracle(ps, n, B):
+    import torch
+    theta = synth.he_uniform_theta(100 + n + B)
+    theta[144:160] = np.linspace(-0.03, 0.03, 16, dtype=np.float32)   # non-zero conv1 biases
+    drop_seed = DROP_SEED + B
+    ctx = ps.ps_init(ps.make_config(n, B, 1, n, drop_seed, P_DROP))
+    try:
+        ps.ps_set_weights(ctx, theta)
+        mbs = [synth.minibatch_id(w, B) for w in range(n)]
+        x, y = synth.minibatches(DATA_SEED + n, mbs, B)
+        xd, yd = _torch_inputs(np.ascontiguousarray(x), np.ascontiguousarray(y))
+        loss = torch.zeros(n, device="cuda")
+        say(f"ragged: launching worker_grads_batched n={n} B={B}")
+        entries = ps.worker_grads_batched(ctx, range(n), [0] * n, mbs, xd, yd, loss)
+        ps.ps_sync(ctx)
+        losses = loss.cpu().numpy()
+        for i in sorted({0, n // 2, n - 1}):
+            r = parity.check_worker(ps, ctx, i, entries[i], theta.astype(np.float64), x[i], y[i], mbs[i], drop_seed, P_DROP,
+                                    f"n={n} B={B} worker {i}")
+            assert abs(losses[i] - r["loss"]) <= 1e-5 * abs(r["loss"])
+            say(f"ragged: n={n} B={B} worker {i} grad rel err max {r['worst']:.2e}")
+    finally:
+        ps.ps_destroy(ctx)
+
+
 def test_gradient_does_not_depend_on_batching(ps):
     """The same logical minibatch gives the same bytes whether computed alone or next to others."""
     B = 16
@@ -295,6 +323,45 @@ def test_full_size_drain_1024(ps, mode):
         parity.assert_close(got, ref, parity.WEIGHT_TOL, "drained weights")
         moved = np.abs(ref - theta0).max()
         assert np.abs(got - ref).max() <= 1e-3 * moved
+    finally:
+        ps.ps_destroy(ctx)
+
+
+@pytest.mark.parametrize("K", [1, 7, 8, 9, 17])
+def test_drains_with_backlogs_around_the_unroll_factor(ps, K):
+    """Every drain form (SUM, SEQ, clipped SEQ, Adadelta) over K rows, K below, at and above the eight rows
+    the kernels stream per pass."""
+    lr, clip, rho, eps = 0.01, 3.0, 0.9, 1e-6
+    theta0 = synth.he_uniform_theta(40 + K)
+    rows = synth.gradient_rows(29, 0, K, ps.P)
+    rows *= np.array([0.5, 1.0, 2.0], np.float32)[np.arange(K) % 3][:, None]
+    pending = list(rows)
+    ctx = ps.ps_init(ps.make_config(1, 1, 1, K, DROP_SEED, P_DROP))
+    try:
+        def fill():
+            ps.ps_set_weights(ctx, theta0)
+            for i in range(K):
+                ps.ps_queue_push_host(ctx, rows[i], 0, 0, i)
+        for mode in (0, 1):
+            fill()
+            assert ps.ps_drain_buffered(ctx, mode, lr) == K
+            parity.assert_close(ps.ps_get_weights(ctx), orc.drain(theta0.astype(np.float64), pending, lr, mode),
+                                parity.WEIGHT_TOL, f"drain mode {mode} K={K}")
+        fill()
+        k, used = ps.ps_drain_buffered_mitigated(ctx, 1, lr, 0.0, clip)
+        assert k == K and abs(used - lr) <= 1e-7 * lr
+        ref = orc.drain_mitigated(theta0.astype(np.float64), pending, lr, 1, 0.0, clip)
+        ref = ref[0] if isinstance(ref, tuple) else ref
+        got = ps.ps_get_weights(ctx)
+        parity.assert_close(got, ref, parity.WEIGHT_TOL, f"clipped drain K={K}")
+        assert np.abs(got - ref).max() <= 1e-3 * np.abs(ref - theta0).max()
+        fill()
+        assert ps.ps_drain_buffered_adadelta(ctx, 1.0, rho, eps) == K
+        ref = orc.drain_adadelta(theta0.astype(np.float64), pending, 1.0, rho, eps, np.zeros(ps.P), np.zeros(ps.P))
+        ref = ref[0] if isinstance(ref, tuple) else ref
+        got = ps.ps_get_weights(ctx)
+        parity.assert_close(got, ref, parity.WEIGHT_TOL, f"Adadelta drain K={K}")
+        assert np.abs(got - ref).max() <= 1e-3 * np.abs(ref - theta0).max()
     finally:
         ps.ps_destroy(ctx)
 
