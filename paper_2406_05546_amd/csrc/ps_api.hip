@@ -92,7 +92,7 @@ Layout make_layout(const ps_config& c)
     l.dp2g = k.take(n * P2_SIZE * 4);
     l.part = k.take((uint64_t)c.max_workers * N_PART * CONV_PART * 4);
     l.part1 = k.take((uint64_t)c.max_workers * conv1_part_slots(c.batch) * OFF_W2 * 4);
-    l.fpart = k.take((uint64_t)4 * (512 + c.max_workers) * FC2_PART * 4);  // >= n * 4 * fc2_split(n) slots
+    l.fpart = k.take((uint64_t)(512 + c.max_workers) * FC2_PART * 4);  // >= n * fc2_split(n) slots
     l.normpart = k.take((uint64_t)c.queue_capacity * norm_slices() * 4);
     l.scale = k.take((uint64_t)c.queue_capacity * 4);
     l.eval_loss = k.take(n * 4);

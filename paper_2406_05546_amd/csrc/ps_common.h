@@ -50,7 +50,7 @@ struct WorkerBuffers {
     float* dp2g;         // [n*B][1568]     d loss / d pool2, zero where pool2 == 0
     float* part;         // [n][N_PART][4800] partial sums of the conv2 weight gradient (conv1 region unused)
     float* part1;        // [n][conv1_part_slots(B)][160] partial sums of the conv1 weight gradient
-    float* fpart;        // [n][4*split][FC2_PART] partial sums of the fc2 kernel's wavefronts
+    float* fpart;        // [n][split][FC2_PART] partial sums of the fc2 kernel's blocks
     float* loss;         // [n] or nullptr
     int32_t n, B;
     uint32_t seed_lo, seed_hi;
@@ -84,7 +84,7 @@ __device__ __forceinline__ float pool_first_max(float v0, float v1, float v2, fl
 // One partial slot of the fc2 kernel: d W4 [10][512], d b4 [10], d b3 [512], summed loss.
 constexpr int FC2_PART_B4 = NCLS * FC1, FC2_PART_B3 = FC2_PART_B4 + NCLS, FC2_PART_LOSS = FC2_PART_B3 + FC1,
               FC2_PART = 5648;
-int fc2_split(int n);  // blocks per worker of the fc2 kernel (4 partial slots each)
+int fc2_split(int n);  // blocks per worker of the fc2 kernel (one partial slot each)
 int conv1_part_slots(int batch);  // conv1 partial slots per worker (one per wavefront of conv2's input-gradient kernel)
 
 void launch_conv1_fwd(const WorkerBuffers& wb, hipStream_t s);

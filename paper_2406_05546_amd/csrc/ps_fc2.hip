@@ -1,141 +1,184 @@
-// fc2 (512 -> 10), softmax cross-entropy and everything of their backward pass that does not need
-// the matrix cores, in one kernel:
+// fc2 (512 -> 10), softmax cross-entropy and everything of their backward pass that the fc1 GEMMs do
+// not do, in one kernel:
 //   z = W4 . h + b4;  loss_i = logsumexp(z) - z[y];  d4 = (softmax(z) - onehot(y)) / B;
 //   d3 = (W4^T d4) / (1-p) where the dropped-and-rectified fc1 activation is > 0, else 0;
 //   per worker: d W4 += d4 (x) h,  d b4 += d4,  d b3 += d3,  loss += loss_i.
-// A wavefront keeps its 10 x 8 slice of W4 and of the d W4 accumulator in registers and walks every
-// (4 * split)-th image of one worker; lane l owns fc1 units l, l+64, ..., l+448.  Each wavefront's
-// sums go to its own partial slot and are added up in fixed order by the reduction kernel.
+// The three contractions run on the matrix cores (v_mfma_f32_16x16x4_f32), 16 images at a time, the
+// ten classes padded to 16.  A block stages the 16 x 512 activations of a group in LDS (the next
+// group's are on their way into registers meanwhile); wavefront v owns fc1 units 128v .. 128v+127:
+//   logits     rows = images, columns = classes, K = this wavefront's 128 units; the four wavefronts'
+//              partial sums meet in LDS and every wavefront then does the (cheap) softmax itself, which
+//              leaves d4 in MFMA accumulator layout: lane (q, l) holds images 4q..4q+3 of class l;
+//   d3         rows = images, columns = this wavefront's units (8 tiles), K = classes; its A operand is
+//              d4 transposed through a wavefront-private LDS tile;
+//   d W4       rows = classes, columns = units, K = images; its A operand is d4 exactly as the
+//              accumulator layout holds it, its B operand the activations that also gate d3.
+// W4 sits in registers in both operand layouts (64 per lane), d W4 in 32 accumulators per lane.  Each
+// block's sums go to its own partial slot and are added up in fixed order by the reduction kernel.
 #include "ps_common.h"
 
 namespace ps {
 
 namespace {
 
-// Sum over the 64 lanes of a wavefront, the same value returned in every lane.  Data-parallel
-// primitives (lane permutes inside the vector ALU) instead of shuffles through the LDS crossbar:
-// butterflies inside quads and rows of 16, then the row sums are passed up rows 0 -> 1, {0,1} -> {2,3},
-// which leaves the total in lane 63.
-__device__ __forceinline__ float wave_sum(float v)
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+constexpr int FC2_G = 16;                 // images per group
+constexpr int FC2_HP = FC1 + 4;           // LDS row pitch of the activation tile (floats)
+constexpr int FC2_TP = 20;                // row pitch of the 16 x 16 transpose tiles
+
+// Lane l of a row of 16 gets op over the 16 lanes of its row (data-parallel primitives: swaps inside
+// quads, then the two mirrors).
+template <class Op>
+__device__ __forceinline__ float row16_reduce(float v, Op op)
 {
-    auto dpp_add = [](float x, int ctrl, int row_mask) {
-        const int moved = 0;  // rows outside the mask add nothing
-        int r;
-        switch (ctrl) {
-            case 0: r = __builtin_amdgcn_update_dpp(moved, __float_as_int(x), 0xB1, 0xF, 0xF, false); break;   // quad_perm [1,0,3,2]
-            case 1: r = __builtin_amdgcn_update_dpp(moved, __float_as_int(x), 0x4E, 0xF, 0xF, false); break;   // quad_perm [2,3,0,1]
-            case 2: r = __builtin_amdgcn_update_dpp(moved, __float_as_int(x), 0x141, 0xF, 0xF, false); break;  // row_half_mirror
-            case 3: r = __builtin_amdgcn_update_dpp(moved, __float_as_int(x), 0x140, 0xF, 0xF, false); break;  // row_mirror
-            case 4: r = __builtin_amdgcn_update_dpp(moved, __float_as_int(x), 0x142, 0xA, 0xF, false); break;  // row_bcast:15 into rows 1, 3
-            default: r = __builtin_amdgcn_update_dpp(moved, __float_as_int(x), 0x143, 0xC, 0xF, false); break; // row_bcast:31 into rows 2, 3
-        }
-        (void)row_mask;
-        return x + __int_as_float(r);
-    };
-    v = dpp_add(v, 0, 0xF);
-    v = dpp_add(v, 1, 0xF);
-    v = dpp_add(v, 2, 0xF);
-    v = dpp_add(v, 3, 0xF);
-    v = dpp_add(v, 4, 0xA);
-    v = dpp_add(v, 5, 0xC);
-    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+    v = op(v, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xF, 0xF, false)));   // quad_perm [1,0,3,2]
+    v = op(v, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xF, 0xF, false)));   // quad_perm [2,3,0,1]
+    v = op(v, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xF, 0xF, false)));  // row_half_mirror
+    v = op(v, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x140, 0xF, 0xF, false)));  // row_mirror
+    return v;
 }
 
 __global__ __launch_bounds__(256, 2) void fc2_kernel(WorkerBuffers wb)
 {
-    const int lane = threadIdx.x & 63, w = blockIdx.x, B = wb.B;
-    const int nsub = 4 * gridDim.y, sub = 4 * blockIdx.y + (threadIdx.x >> 6);
+    __shared__ __attribute__((aligned(16))) float hs[2][FC2_G * FC2_HP];     // 66,048 B
+    __shared__ __attribute__((aligned(16))) float zpart[4 * 64 * 4];         // the wavefronts' partial logits
+    __shared__ __attribute__((aligned(16))) float d4t[4][FC2_G * FC2_TP];    // wavefront-private transposes
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, q = lane >> 4, l16 = lane & 15;
+    const int w = blockIdx.x, B = wb.B, split = gridDim.y, n_groups = (B + FC2_G - 1) / FC2_G;
     const float* __restrict__ theta = worker_theta(wb, w);
-    float w4[NCLS][8], acc[NCLS][8], accb3[8], accb4[NCLS], b4[NCLS];
+    const float* __restrict__ W4 = theta + OFF_W4;
+    const bool cls_ok = l16 < NCLS;
+    const int u0 = 128 * wave;
+
+    // B operand of the logits: k-step (j, e) pairs lane quarter q with unit u0 + 16j + 4q + e
+    float wa[8][4];
 #pragma unroll
-    for (int c = 0; c < NCLS; ++c) {
+    for (int j = 0; j < 8; ++j)
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            w4[c][j] = theta[OFF_W4 + c * FC1 + lane + 64 * j];
-            acc[c][j] = 0.f;
-        }
-        accb4[c] = 0.f;
-        b4[c] = theta[OFF_B4 + c];
-    }
+        for (int e = 0; e < 4; ++e) wa[j][e] = cls_ok ? W4[l16 * FC1 + u0 + 16 * j + 4 * q + e] : 0.f;
+    // B operand of d3: tile t, k-step i pairs lane quarter q with class 4q + i; column l16 = unit u0 + 16t + l16
+    float wbk[8][4];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) accb3[j] = 0.f;
-    float loss = 0.f;
+    for (int t = 0; t < 8; ++t)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) wbk[t][i] = 4 * q + i < NCLS ? W4[(4 * q + i) * FC1 + u0 + 16 * t + l16] : 0.f;
+    const float b4 = cls_ok ? theta[OFF_B4 + l16] : 0.f;
     const float inv_b = 1.f / (float)B;
 
-    float hn[8];
-    if (sub < B) {
+    floatx4 acc_w4[8];  // d W4 tile t: register i = class 4q + i, column l16 = unit u0 + 16t + l16
+    float acc_b3[8], acc_b4 = 0.f, acc_loss = 0.f;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) hn[j] = wb.ht[((size_t)w * B + sub) * FC1 + lane + 64 * j];
-    }
-    for (int s = sub; s < B; s += nsub) {
-        const size_t g = (size_t)w * B + s;
-        float hv[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) hv[j] = hn[j];
-        if (s + nsub < B) {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) hn[j] = wb.ht[(g + nsub) * FC1 + lane + 64 * j];
-        }
-        float z[NCLS];
-#pragma unroll
-        for (int c = 0; c < NCLS; ++c) {
-            float part = 0.f;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) part = fmaf(hv[j], w4[c][j], part);
-            z[c] = wave_sum(part) + b4[c];
-        }
-        const int label = wb.y[g];
-        float zmax = z[0];
-        int pred = 0;
-#pragma unroll
-        for (int c = 1; c < NCLS; ++c)
-            if (z[c] > zmax) { zmax = z[c]; pred = c; }
-        float e[NCLS], se = 0.f;
-#pragma unroll
-        for (int c = 0; c < NCLS; ++c) {
-            e[c] = expf(z[c] - zmax);
-            se += e[c];
-        }
-        const float lse = zmax + logf(se), inv_se = 1.f / se;
-        float d4[NCLS], zy = 0.f;
-#pragma unroll
-        for (int c = 0; c < NCLS; ++c) {
-            d4[c] = (e[c] * inv_se - (c == label ? 1.f : 0.f)) * inv_b;
-            if (c == label) zy = z[c];
-            accb4[c] += d4[c];
-        }
-        loss += lse - zy;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            float dh = 0.f;
-#pragma unroll
-            for (int c = 0; c < NCLS; ++c) {
-                dh = fmaf(d4[c], w4[c][j], dh);
-                acc[c][j] = fmaf(d4[c], hv[j], acc[c][j]);
-            }
-            const float d3 = hv[j] > 0.f ? dh * wb.drop_scale : 0.f;
-            wb.d3[g * FC1 + lane + 64 * j] = d3;
-            accb3[j] += d3;
-        }
-        float zl = 0.f;
-#pragma unroll
-        for (int c = 0; c < NCLS; ++c)
-            if (lane == c) zl = z[c];
-        if (lane < NCLS) wb.z[g * NCLS + lane] = zl;
-        if (lane == 0) wb.pred[g] = pred;
+    for (int t = 0; t < 8; ++t) {
+        acc_w4[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+        acc_b3[t] = 0.f;
     }
 
-    float* part = wb.fpart + ((size_t)w * nsub + sub) * FC2_PART;
+    // activations of a group: 16 x 128 float4, eight per thread; rows beyond the batch are zero
+    float4 hv[8];
+    auto prefetch = [&](int grp) {
+        const size_t g0 = (size_t)w * B + (size_t)grp * FC2_G;
+        const int valid = min(FC2_G, B - grp * FC2_G);
 #pragma unroll
-    for (int c = 0; c < NCLS; ++c)
+        for (int k = 0; k < 8; ++k) {
+            const int f = tid + 256 * k, img = f >> 7, c4 = f & 127;
+            hv[k] = img < valid ? *reinterpret_cast<const float4*>(wb.ht + (g0 + img) * FC1 + 4 * c4) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    };
+    int grp = blockIdx.y, buf = 0;
+    if (grp < n_groups) prefetch(grp);
+    for (; grp < n_groups; grp += split, buf ^= 1) {
+        const size_t g0 = (size_t)w * B + (size_t)grp * FC2_G;
+        const int valid = min(FC2_G, B - grp * FC2_G);
+        float* __restrict__ hb = hs[buf];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) part[c * FC1 + lane + 64 * j] = acc[c][j];
+        for (int k = 0; k < 8; ++k) {
+            const int f = tid + 256 * k, img = f >> 7, c4 = f & 127;
+            *reinterpret_cast<float4*>(hb + img * FC2_HP + 4 * c4) = hv[k];
+        }
+        __syncthreads();  // also: every wavefront is done with the group before last, whose buffer comes next
+        if (grp + split < n_groups) prefetch(grp + split);
+        int label[4];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) part[FC2_PART_B3 + lane + 64 * j] = accb3[j];
-    if (lane == 0) {
+        for (int i = 0; i < 4; ++i) label[i] = 4 * q + i < valid ? wb.y[g0 + 4 * q + i] : -1;
+
+        // logits, this wavefront's share of K: rows = images (lane row l16), columns = classes
+        floatx4 zacc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int c = 0; c < NCLS; ++c) part[FC2_PART_B4 + c] = accb4[c];
-        part[FC2_PART_LOSS] = loss;
+        for (int j = 0; j < 8; ++j) {
+            const floatx4 a = *reinterpret_cast<const floatx4*>(hb + l16 * FC2_HP + u0 + 16 * j + 4 * q);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) zacc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[e], wa[j][e], zacc, 0, 0, 0);
+        }
+        *reinterpret_cast<floatx4*>(zpart + (wave * 64 + lane) * 4) = zacc;
+        __syncthreads();
+        floatx4 z = *reinterpret_cast<const floatx4*>(zpart + lane * 4);
+#pragma unroll
+        for (int v = 1; v < 4; ++v) z += *reinterpret_cast<const floatx4*>(zpart + (v * 64 + lane) * 4);
+
+        // softmax and d4 for images 4q + i, class l16 (classes 10..15 are padding)
+        floatx4 d4;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float zi = z[i] + b4;
+            const float zmax = row16_reduce(cls_ok ? zi : -INFINITY, [](float a, float b) { return fmaxf(a, b); });
+            const float e = cls_ok ? expf(zi - zmax) : 0.f;
+            const float se = row16_reduce(e, [](float a, float b) { return a + b; });
+            const bool img_ok = label[i] >= 0, mine = l16 == label[i];
+            d4[i] = (img_ok && cls_ok) ? (e * (1.f / se) - (mine ? 1.f : 0.f)) * inv_b : 0.f;
+            if (wave == 0) {
+                if (mine) acc_loss += zmax + logf(se) - zi;
+                acc_b4 += d4[i];
+                const float first = row16_reduce((cls_ok && zi == zmax) ? (float)l16 : 99.f, [](float a, float b) { return fminf(a, b); });
+                if (img_ok && cls_ok) wb.z[(g0 + 4 * q + i) * NCLS + l16] = zi;
+                if (img_ok && l16 == 0) wb.pred[g0 + 4 * q + i] = (int)first;
+            }
+        }
+
+        // d4 with images along the lane rows, for the A operand of d3 (wavefront-private: no barrier)
+        float* tp = d4t[wave];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) tp[(4 * q + i) * FC2_TP + l16] = d4[i];
+        const floatx4 d4a = *reinterpret_cast<const floatx4*>(tp + l16 * FC2_TP + 4 * q);
+
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            // activations of images 4q + i at unit u0 + 16t + l16: gate of d3 and B operand of d W4
+            float hc[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) hc[i] = hb[(4 * q + i) * FC2_HP + u0 + 16 * t + l16];
+            floatx4 dh = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) dh = __builtin_amdgcn_mfma_f32_16x16x4f32(d4a[i], wbk[t][i], dh, 0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc_w4[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(d4[i], hc[i], acc_w4[t], 0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float d3 = hc[i] > 0.f ? dh[i] * wb.drop_scale : 0.f;
+                if (4 * q + i < valid) wb.d3[(g0 + 4 * q + i) * FC1 + u0 + 16 * t + l16] = d3;
+                acc_b3[t] += d3;
+            }
+        }
+    }
+
+    float* part = wb.fpart + ((size_t)w * split + blockIdx.y) * FC2_PART;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (4 * q + i < NCLS) part[(4 * q + i) * FC1 + u0 + 16 * t + l16] = acc_w4[t][i];
+        float s = acc_b3[t];  // the four lane quarters hold different images
+        s += __shfl_xor(s, 16, 64);
+        s += __shfl_xor(s, 32, 64);
+        if (q == 0) part[FC2_PART_B3 + u0 + 16 * t + l16] = s;
+    }
+    if (wave == 0) {
+        acc_b4 += __shfl_xor(acc_b4, 16, 64);
+        acc_b4 += __shfl_xor(acc_b4, 32, 64);
+        if (q == 0 && cls_ok) part[FC2_PART_B4 + l16] = acc_b4;
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) acc_loss += __shfl_xor(acc_loss, off, 64);
+        if (lane == 0) part[FC2_PART_LOSS] = acc_loss;
     }
 }
 

@@ -13,7 +13,7 @@ namespace {
 
 // Sums the partial slots in fixed order into the worker's queue entry: conv1 tensors have one partial
 // per wavefront of conv2's input-gradient kernel, conv2 tensors one per (chunk, wavefront) of its
-// weight-gradient kernel, fc2 tensors, fc1 bias and the loss one per wavefront of the fc2 kernel.
+// weight-gradient kernel, fc2 tensors, fc1 bias and the loss one per block of the fc2 kernel.
 __global__ __launch_bounds__(256) void grad_reduce_kernel(WorkerBuffers wb, int fc2_slots, int c1_slots)
 {
     const int w = blockIdx.x;
@@ -86,7 +86,7 @@ hipError_t launch_worker_backward(const WorkerBuffers& wb, hipStream_t s, Profil
     PS_TIMED(K_FC1_DX, launch_fc1_dx(wb, s));
     PS_TIMED(K_CONV2_DW, launch_conv2_dw(wb, s));
     PS_TIMED(K_CONV2_DX, launch_conv2_dx(wb, s));
-    PS_TIMED(K_GRAD_REDUCE, hipLaunchKernelGGL(grad_reduce_kernel, dim3(wb.n, 8), dim3(256), 0, s, wb, 4 * fc2_split(wb.n),
+    PS_TIMED(K_GRAD_REDUCE, hipLaunchKernelGGL(grad_reduce_kernel, dim3(wb.n, 8), dim3(256), 0, s, wb, fc2_split(wb.n),
                                                 conv1_part_slots(wb.B)));
     return hipGetLastError();
 }
