@@ -10,7 +10,9 @@
 //              partial sums meet in LDS and every wavefront then does the (cheap) softmax itself, which
 //              leaves d4 in MFMA accumulator layout: lane (q, l) holds images 4q..4q+3 of class l;
 //   d3         rows = images, columns = this wavefront's units (8 tiles), K = classes; its A operand is
-//              d4 transposed through a wavefront-private LDS tile;
+//              d4 transposed through a wavefront-private LDS tile.  Column l of tile (T, e) is unit
+//              128v + 64T + 4l + e, so that a lane's values of the four tiles e = 0..3 are four
+//              consecutive units: one 16-byte LDS read for the gate, one 16-byte store for d3;
 //   d W4       rows = classes, columns = units, K = images; its A operand is d4 exactly as the
 //              accumulator layout holds it, its B operand the activations that also gate d3.
 // W4 sits in registers in both operand layouts (64 per lane), d W4 in 32 accumulators per lane.  Each
@@ -57,16 +59,18 @@ __global__ __launch_bounds__(256, 2) void fc2_kernel(WorkerBuffers wb)
     for (int j = 0; j < 8; ++j)
 #pragma unroll
         for (int e = 0; e < 4; ++e) wa[j][e] = cls_ok ? W4[l16 * FC1 + u0 + 16 * j + 4 * q + e] : 0.f;
-    // B operand of d3: tile t, k-step i pairs lane quarter q with class 4q + i; column l16 = unit u0 + 16t + l16
+    // B operand of d3: tile t = 4T + e, k-step i pairs lane quarter q with class 4q + i; column l16 = unit
+    // u0 + 64T + 4*l16 + e
     float wbk[8][4];
 #pragma unroll
     for (int t = 0; t < 8; ++t)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) wbk[t][i] = 4 * q + i < NCLS ? W4[(4 * q + i) * FC1 + u0 + 16 * t + l16] : 0.f;
+        for (int i = 0; i < 4; ++i)
+            wbk[t][i] = 4 * q + i < NCLS ? W4[(4 * q + i) * FC1 + u0 + 64 * (t >> 2) + 4 * l16 + (t & 3)] : 0.f;
     const float b4 = cls_ok ? theta[OFF_B4 + l16] : 0.f;
     const float inv_b = 1.f / (float)B;
 
-    floatx4 acc_w4[8];  // d W4 tile t: register i = class 4q + i, column l16 = unit u0 + 16t + l16
+    floatx4 acc_w4[8];  // d W4 tile t = 4T + e: register i = class 4q + i, column l16 = unit u0 + 64T + 4*l16 + e
     float acc_b3[8], acc_b4 = 0.f, acc_loss = 0.f;
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
@@ -142,35 +146,55 @@ __global__ __launch_bounds__(256, 2) void fc2_kernel(WorkerBuffers wb)
         const floatx4 d4a = *reinterpret_cast<const floatx4*>(tp + l16 * FC2_TP + 4 * q);
 
 #pragma unroll
-        for (int t = 0; t < 8; ++t) {
-            // activations of images 4q + i at unit u0 + 16t + l16: gate of d3 and B operand of d W4
-            float hc[4];
+        for (int T = 0; T < 2; ++T) {
+            // activations of images 4q + i at units u0 + 64T + 4*l16 .. +3: gate of d3 and B operand of d W4
+            floatx4 hc[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) hc[i] = hb[(4 * q + i) * FC2_HP + u0 + 16 * t + l16];
-            floatx4 dh = {0.f, 0.f, 0.f, 0.f};
+            for (int i = 0; i < 4; ++i) hc[i] = *reinterpret_cast<const floatx4*>(hb + (4 * q + i) * FC2_HP + u0 + 64 * T + 4 * l16);
+            floatx4 dh[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) dh = __builtin_amdgcn_mfma_f32_16x16x4f32(d4a[i], wbk[t][i], dh, 0, 0, 0);
+            for (int e = 0; e < 4; ++e) {
+                dh[e] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int i = 0; i < 4; ++i) acc_w4[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(d4[i], hc[i], acc_w4[t], 0, 0, 0);
+                for (int i = 0; i < 4; ++i) dh[e] = __builtin_amdgcn_mfma_f32_16x16x4f32(d4a[i], wbk[4 * T + e][i], dh[e], 0, 0, 0);
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    acc_w4[4 * T + e] = __builtin_amdgcn_mfma_f32_16x16x4f32(d4[i], hc[i][e], acc_w4[4 * T + e], 0, 0, 0);
+            }
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const float d3 = hc[i] > 0.f ? dh[i] * wb.drop_scale : 0.f;
-                if (4 * q + i < valid) wb.d3[(g0 + 4 * q + i) * FC1 + u0 + 16 * t + l16] = d3;
-                acc_b3[t] += d3;
+                floatx4 d3;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    d3[e] = hc[i][e] > 0.f ? dh[e][i] * wb.drop_scale : 0.f;
+                    acc_b3[4 * T + e] += d3[e];
+                }
+                if (4 * q + i < valid) *reinterpret_cast<floatx4*>(wb.d3 + (g0 + 4 * q + i) * FC1 + u0 + 64 * T + 4 * l16) = d3;
             }
         }
     }
 
     float* part = wb.fpart + ((size_t)w * split + blockIdx.y) * FC2_PART;
 #pragma unroll
-    for (int t = 0; t < 8; ++t) {
+    for (int T = 0; T < 2; ++T) {
+        const int u = u0 + 64 * T + 4 * l16;
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            if (4 * q + i < NCLS) part[(4 * q + i) * FC1 + u0 + 16 * t + l16] = acc_w4[t][i];
-        float s = acc_b3[t];  // the four lane quarters hold different images
-        s += __shfl_xor(s, 16, 64);
-        s += __shfl_xor(s, 32, 64);
-        if (q == 0) part[FC2_PART_B3 + u0 + 16 * t + l16] = s;
+            if (4 * q + i < NCLS)
+                *reinterpret_cast<floatx4*>(part + (4 * q + i) * FC1 + u) =
+                    floatx4{acc_w4[4 * T][i], acc_w4[4 * T + 1][i], acc_w4[4 * T + 2][i], acc_w4[4 * T + 3][i]};
+        floatx4 b3;  // the four lane quarters hold different images
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            float v = acc_b3[4 * T + e];
+            v += __shfl_xor(v, 16, 64);
+            v += __shfl_xor(v, 32, 64);
+            b3[e] = v;
+        }
+        if (q == 0) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) part[FC2_PART_B3 + u + e] = b3[e];
+        }
     }
     if (wave == 0) {
         acc_b4 += __shfl_xor(acc_b4, 16, 64);
