@@ -129,7 +129,7 @@ template <class Cfg, bool RAGGED, class Epi>
 __device__ __forceinline__ void gemm_block(const GemmShape& sh, const Epi& epi, int block, float* __restrict__ lds)
 {
     constexpr bool A_KC = Cfg::A_KC, B_KC = Cfg::B_KC;
-    constexpr int TM = Cfg::TM, TN = Cfg::TN, WM = Cfg::WM, WN = Cfg::WN, KS = Cfg::KS, BM = Cfg::BM, BN = Cfg::BN;
+    constexpr int TM = Cfg::TM, TN = Cfg::TN, WM = Cfg::WM, KS = Cfg::KS, BM = Cfg::BM, BN = Cfg::BN;
     using OpA = GemmOperand<BM, KS, A_KC, RAGGED>;
     using OpB = GemmOperand<BN, KS, B_KC, RAGGED>;
     constexpr int STAGE = OpA::FLOATS + OpB::FLOATS;
