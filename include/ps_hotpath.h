@@ -189,6 +189,12 @@ PS_API ps_status ps_elastic_average(ps_ctx* ctx, const int32_t* slot_host, int32
  * N updates by the caller. */
 PS_API ps_status ps_restore_weights(ps_ctx* ctx, int32_t slot, int32_t* n_dropped_host);
 
+/* Loads a ring slot from host memory: ring[slot] := theta_host[P], recorded as the snapshot taken at
+ * `version` (Section 2.1: a restarted server rehydrates the latest checkpoint from persistent storage;
+ * followed by ps_restore_weights(slot) this is that path, and it also restores a worker-local copy).
+ * The server's weights and version do not change.  Waits for the copy. */
+PS_API ps_status ps_load_snapshot(ps_ctx* ctx, int32_t slot, const float* theta_host, uint64_t version);
+
 /* Periodic evaluation (Section 3.1: accuracy and loss are collected periodically): inference forward
  * pass without dropout on n_images images x_dev[n_images][784] with labels y_dev[n_images], using the
  * server's current weights (slot = -1) or ring slot `slot`.  n_images must be a positive multiple
@@ -216,7 +222,9 @@ PS_API ps_status ps_evaluate(ps_ctx* ctx, int32_t slot, int32_t n_images, const 
  * While the store holds gradients that the host has not yet seen consumed (ps_store_state tells),
  * the calls above that touch the queue or the server's weights return PS_ESTATE; the store calls in
  * turn need the pending queue of those calls to be empty.  Version counts and snapshot versions carry
- * over in both directions.  ps_get_weights, ps_evaluate and ps_sync wait for both streams. */
+ * over in both directions: the first store call hands them to the device, and the first of the calls
+ * above after store calls waits for both streams and takes them back (no ps_store_state needed in
+ * between).  ps_get_weights, ps_evaluate and ps_sync wait for both streams. */
 
 typedef struct {
     uint64_t claimed;   /* gradients ever appended (positions handed out)               */
@@ -280,7 +288,7 @@ PS_API ps_status ps_queue_meta(ps_ctx* ctx, int32_t capacity, int32_t* n_host, u
                         int32_t* worker_host, uint64_t* version_host, uint64_t* minibatch_host,
                         int32_t* queue_index_host);
 
-/* Number of weight updates applied so far. */
+/* Number of weight updates applied so far.  After lock-free store calls this waits for both streams. */
 PS_API ps_status ps_version(ps_ctx* ctx, uint64_t* version_host);
 
 /* Decisions taken for worker i of the most recent worker_grads_batched call (any pointer may be
@@ -291,6 +299,16 @@ PS_API ps_status ps_version(ps_ctx* ctx, uint64_t* version_host);
  * (lowest index on ties). */
 PS_API ps_status ps_debug_last_batch(ps_ctx* ctx, int32_t i, uint8_t* pool1_host, uint8_t* pool2_host,
                               uint8_t* keep_host, float* hdrop_host, float* z_host, int32_t* pred_host);
+
+/* Values behind those decisions, for the same worker of the same call (any pointer may be NULL):
+ * pool1_val_host[B][3136] and pool2_val_host[B][1568] the pooled activations after ReLU (model
+ * endnote: conv, ReLU, max pool), d3_host[B][512] the gradient of the worker's mean loss with
+ * respect to the fc1 pre-activations (zero exactly where the unit was dropped or its ReLU was
+ * off), dpool2_host[B][1568] the gradient with respect to the pool2 outputs, zero where the pooled
+ * activation is zero.  Tests measure the fp32 rounding of each layer from these and check that the
+ * backward pass used the same dropout mask as the forward pass. */
+PS_API ps_status ps_debug_last_activations(ps_ctx* ctx, int32_t i, float* pool1_val_host, float* pool2_val_host,
+                                           float* d3_host, float* dpool2_host);
 
 /* Per-kernel timing (instrumentation, not part of the method).  While enabled, every kernel launch
  * of this context is bracketed by two HIP events on the context's stream.  ps_profile_enable waits

@@ -27,9 +27,9 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libps_hotpa
 
 EXPORTS = ["ps_workspace_bytes", "ps_init", "ps_destroy", "ps_sync", "ps_set_weights", "ps_get_weights",
            "ps_snapshot_weights", "worker_grads_batched", "ps_queue_push_host", "ps_apply_sync", "ps_apply_async",
-           "ps_drain_buffered", "ps_drain_buffered_mitigated", "ps_drain_buffered_adadelta", "ps_apply_local", "ps_elastic_average", "ps_restore_weights", "ps_evaluate",
+           "ps_drain_buffered", "ps_drain_buffered_mitigated", "ps_drain_buffered_adadelta", "ps_apply_local", "ps_elastic_average", "ps_restore_weights", "ps_load_snapshot", "ps_evaluate",
            "worker_grads_append", "ps_store_consume", "ps_store_publish", "ps_store_state", "ps_store_steps",
-           "ps_store_entry", "ps_get_grad", "ps_queue_meta", "ps_version", "ps_debug_last_batch", "ps_profile_enable",
+           "ps_store_entry", "ps_get_grad", "ps_queue_meta", "ps_version", "ps_debug_last_batch", "ps_debug_last_activations", "ps_profile_enable",
            "ps_profile_read", "ps_profile_kernel_count", "ps_profile_kernel_name", "ps_last_error"]
 
 
@@ -89,6 +89,7 @@ def load_library() -> ctypes.CDLL:
             "ps_apply_local": [vp, i32, vp, vp, f32],
             "ps_elastic_average": [vp, vp, i32, f32],
             "ps_restore_weights": [vp, i32, ctypes.POINTER(i32)],
+            "ps_load_snapshot": [vp, i32, vp, u64],
             "ps_evaluate": [vp, i32, i32, vp, vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double), vp],
             "worker_grads_append": [vp, i32, vp, vp, vp, vp, vp, vp],
             "ps_store_consume": [vp, i32, f32, i32, i32],
@@ -100,6 +101,7 @@ def load_library() -> ctypes.CDLL:
             "ps_queue_meta": [vp, i32, ctypes.POINTER(i32), vp, vp, vp, vp, vp],
             "ps_version": [vp, ctypes.POINTER(u64)],
             "ps_debug_last_batch": [vp, i32, vp, vp, vp, vp, vp, vp],
+            "ps_debug_last_activations": [vp, i32, vp, vp, vp, vp],
             "ps_profile_enable": [vp, i32],
             "ps_profile_read": [vp, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)],
         }
@@ -281,6 +283,12 @@ def ps_restore_weights(ctx: Context, slot: int) -> int:
     return int(n.value)
 
 
+def ps_load_snapshot(ctx: Context, slot: int, theta: np.ndarray, version: int) -> None:
+    theta = _np(theta, np.float32)
+    assert theta.shape == (P,)
+    _check(ctx, "ps_load_snapshot", load_library().ps_load_snapshot(ctx.handle, slot, _vp(theta), version))
+
+
 def ps_evaluate(ctx: Context, slot: int, x_dev, y_dev) -> Tuple[float, float, np.ndarray]:
     """x_dev: torch float32 cuda [n_images, 784]; y_dev: torch int32 cuda [n_images].
     Returns (mean loss, accuracy, predicted classes)."""
@@ -380,6 +388,16 @@ def ps_debug_last_batch(ctx: Context, i: int) -> dict:
     st = load_library().ps_debug_last_batch(ctx.handle, i, _vp(out["pool1"]), _vp(out["pool2"]), _vp(out["keep"]),
                                             _vp(out["hdrop"]), _vp(out["z"]), _vp(out["pred"]))
     _check(ctx, "ps_debug_last_batch", st)
+    return out
+
+
+def ps_debug_last_activations(ctx: Context, i: int) -> dict:
+    B = ctx.cfg.batch
+    out = {"pool1_val": np.empty((B, POOL1_SIZE), np.float32), "pool2_val": np.empty((B, POOL2_SIZE), np.float32),
+           "d3": np.empty((B, FC1_UNITS), np.float32), "dpool2": np.empty((B, POOL2_SIZE), np.float32)}
+    st = load_library().ps_debug_last_activations(ctx.handle, i, _vp(out["pool1_val"]), _vp(out["pool2_val"]), _vp(out["d3"]),
+                                                  _vp(out["dpool2"]))
+    _check(ctx, "ps_debug_last_activations", st)
     return out
 
 

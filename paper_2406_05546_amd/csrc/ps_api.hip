@@ -287,12 +287,22 @@ bool store_open(ps_ctx* c)
 
 // Entry check of the calls that work on the ordered queue or the server's weights from the worker
 // stream: not while the store holds gradients; ordered after the server stream's work.
+ps_status store_read(ps_ctx* c, StoreState* state, std::vector<unsigned long long>* stamps);
+
 ps_status ordered_guard(ps_ctx* c, const char* who)
 {
     if (store_open(c))
         return fail(c, PS_ESTATE, std::string(who) + ": the lock-free store holds gradients not yet seen consumed "
                                                      "(consume them, then ps_store_state)");
-    c->store_synced = false;
+    if (c->store_synced) {
+        // The device holds the authoritative version counters while the store is in use: take them
+        // back (update count, snapshot versions) before the host's copies are used again.
+        StoreState s{};
+        const ps_status st = store_read(c, &s, nullptr);
+        if (st != PS_OK) return st;
+        if (s.head != s.tail) return fail(c, PS_ESTATE, std::string(who) + ": the lock-free store still holds gradients");
+        c->store_synced = false;
+    }
     return workers_wait_server(c);
 }
 
@@ -858,6 +868,18 @@ ps_status ps_restore_weights(ps_ctx* c, int32_t slot, int32_t* n_dropped_host)
     return PS_OK;
 }
 
+ps_status ps_load_snapshot(ps_ctx* c, int32_t slot, const float* theta_host, uint64_t version)
+{
+    if (!c || !theta_host) return fail(c, PS_EINVAL, "ps_load_snapshot: null argument");
+    if (slot < 0 || slot >= c->cfg.n_versions) return fail(c, PS_EINVAL, "ps_load_snapshot: slot out of range");
+    { const ps_status g_ = ordered_guard(c, "ps_load_snapshot"); if (g_ != PS_OK) return g_; }
+    // the row's padding beyond P stays zero: it was zero after ps_init and every copy into it carries zeros there
+    PS_HIP(c, hipMemcpyAsync(c->ring(slot), theta_host, sizeof(float) * P, hipMemcpyHostToDevice, c->stream));
+    PS_HIP(c, hipStreamSynchronize(c->stream));
+    c->ring_version[slot] = version;
+    return PS_OK;
+}
+
 ps_status ps_evaluate(ps_ctx* c, int32_t slot, int32_t n_images, const float* x_dev, const int32_t* y_dev,
                       double* loss_host, double* accuracy_host, int32_t* pred_host)
 {
@@ -902,6 +924,11 @@ ps_status ps_evaluate(ps_ctx* c, int32_t slot, int32_t n_images, const float* x_
 ps_status ps_version(ps_ctx* c, uint64_t* version_host)
 {
     if (!c || !version_host) return PS_EINVAL;
+    if (c->store_synced) {  // the count lives on the device while the store is in use
+        StoreState s{};
+        const ps_status st = store_read(c, &s, nullptr);
+        if (st != PS_OK) return st;
+    }
     *version_host = c->version;
     return PS_OK;
 }
@@ -925,6 +952,22 @@ ps_status ps_debug_last_batch(ps_ctx* c, int32_t i, uint8_t* pool1_host, uint8_t
                                    wb.drop_threshold, s));
         PS_HIP(c, hipMemcpyAsync(keep_host, c->at<uint8_t>(c->lay.keep), B * FC1, hipMemcpyDeviceToHost, s));
     }
+    PS_HIP(c, hipStreamSynchronize(s));
+    return PS_OK;
+}
+
+ps_status ps_debug_last_activations(ps_ctx* c, int32_t i, float* pool1_val_host, float* pool2_val_host, float* d3_host,
+                                    float* dpool2_host)
+{
+    if (!c) return PS_EINVAL;
+    if (i < 0 || i >= (int32_t)c->last_meta.size())
+        return fail(c, PS_EINVAL, "ps_debug_last_activations: no such worker in the last call");
+    const size_t B = c->cfg.batch, g0 = (size_t)i * B;
+    hipStream_t s = c->stream;
+    if (pool1_val_host) PS_HIP(c, hipMemcpyAsync(pool1_val_host, c->at<float>(c->lay.p1) + g0 * P1_SIZE, B * P1_SIZE * 4, hipMemcpyDeviceToHost, s));
+    if (pool2_val_host) PS_HIP(c, hipMemcpyAsync(pool2_val_host, c->at<float>(c->lay.p2) + g0 * P2_SIZE, B * P2_SIZE * 4, hipMemcpyDeviceToHost, s));
+    if (d3_host) PS_HIP(c, hipMemcpyAsync(d3_host, c->at<float>(c->lay.d3) + g0 * FC1, B * FC1 * 4, hipMemcpyDeviceToHost, s));
+    if (dpool2_host) PS_HIP(c, hipMemcpyAsync(dpool2_host, c->at<float>(c->lay.dp2g) + g0 * P2_SIZE, B * P2_SIZE * 4, hipMemcpyDeviceToHost, s));
     PS_HIP(c, hipStreamSynchronize(s));
     return PS_OK;
 }

@@ -28,6 +28,7 @@ class Replay:
         self.losses: Dict[int, float] = {}
         self.evals: List[tuple] = []         # (eval_id, loss, accuracy, predictions)
         self.dropped: List[int] = []         # pending gradients lost at each restore
+        self.last_inputs = None              # (x, y host arrays, x, y device tensors) of the latest worker step
 
     def close(self):
         ps.ps_destroy(self.ctx)
@@ -43,6 +44,7 @@ class Replay:
                 xd = torch.from_numpy(x).to(self.device)
                 yd = torch.from_numpy(y).to(self.device)
                 loss = torch.empty(len(workers), dtype=torch.float32, device=self.device)
+                self.last_inputs = (x, y, xd, yd)
                 entries = ps.worker_grads_batched(self.ctx, workers, slots, mbs, xd, yd, loss)
                 seqs = list(range(self.next_seq, self.next_seq + len(workers)))
                 self.next_seq += len(workers)

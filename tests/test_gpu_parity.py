@@ -50,11 +50,13 @@ def test_one_call_decisions_gradients_and_stale_slots(ps):
     try:
         # two-version ring: slot 0 = a, slot 1 = b (reached by one async update from a)
         ps.ps_set_weights(ctx, theta_a)
-        g = ps.ps_queue_push_host(ctx, (theta_a - theta_b).astype(np.float32), 9, 0, 0)
+        step = (theta_a - theta_b).astype(np.float32)
+        g = ps.ps_queue_push_host(ctx, step, 9, 0, 0)
         ps.ps_apply_async(ctx, g, 1.0)                                # theta = a - (a - b) = b
         ps.ps_snapshot_weights(ctx, 1)
         got_b = ps.ps_get_weights(ctx, 1)
-        assert np.allclose(got_b, theta_b, rtol=0, atol=1e-6)
+        ref_b = orc.apply_async(theta_a.astype(np.float64), step, 1.0)  # the oracle's own copy of that snapshot
+        assert np.allclose(got_b, theta_b, rtol=0, atol=1e-6) and np.abs(got_b - ref_b).max() <= 1e-7
         assert np.array_equal(ps.ps_get_weights(ctx, 0), theta_a)
         workers, slots = [4, 2, 7], [0, 1, 1]
         mbs = [synth.minibatch_id(w, 3) for w in workers]
@@ -71,10 +73,11 @@ def test_one_call_decisions_gradients_and_stale_slots(ps):
             [(1, 4, 0, mbs[0], 0), (2, 2, 1, mbs[1], 1), (3, 7, 1, mbs[2], 2)]
         losses = loss.cpu().numpy()
         for i in range(n):
-            th = (theta_a if slots[i] == 0 else got_b).astype(np.float64)
+            th = theta_a.astype(np.float64) if slots[i] == 0 else ref_b
             r = parity.check_worker(ps, ctx, i, entries[i], th, x[i], y[i], mbs[i], DROP_SEED, P_DROP, f"worker {i}")
             assert abs(losses[i] - r["loss"]) <= 1e-5 * abs(r["loss"])
-            say(f"one_call: worker {i} grad rel err max {r['worst']:.2e}, near-ties {r['near_ties']}, forced {r['forced']}")
+            say(f"one_call: worker {i} grad rel err max {r['worst']:.2e} (elementwise {r['worst_elementwise']:.2e}), "
+                f"near-ties {r['near_ties']}, forced {r['forced']}")
     finally:
         ps.ps_destroy(ctx)
 
@@ -137,62 +140,120 @@ def test_gradient_does_not_depend_on_batching(ps):
 
 # ------------------------------------------------------------------ the evaluation configurations
 
-def _replay_both(ps, sc, check_every=1, n_threads=0, tie_tol=1e-4):
-    """Both sides replay the scenario event by event; after every worker step the gradients are
-    compared (every `check_every`-th arrival), at the end the weights and the queue metadata."""
+def _replay_both(ps, sc, check_every=1, n_threads=0, progress_every=0):
+    """The HIP path and the oracle replay the scenario event by event.  Compared: every
+    `check_every`-th gradient (1e-4), losses, queue metadata and versions (bit-exact), every published
+    snapshot and the weights at the end (1e-3).
+
+    The gradient is a discontinuous (max, ReLU) and steep function of the weights, and fp32 weights walk
+    away from fp64 ones by about 2^-25 per update, so two runs that each read their own snapshots part
+    within a few steps whatever the kernels do (the drift study beside the oracle shows it with exact
+    gradient arithmetic).  Gradient parity is therefore stated on the same snapshot: after every
+    publish, the slot the HIP path has just written is compared with the oracle's and then loaded with
+    the oracle's snapshot rounded to fp32, so that every worker step of both sides reads the same weights.
+    The updates themselves (every apply and drain, 3,200 of them in the largest case) are the HIP
+    path's own and are never resynchronised.  A max / ReLU decision inside the rounding reach of a tie
+    is taken by the oracle the way the HIP path took it, after checking that it is one of the valid
+    outcomes, so that both runs stay on one branch.
+
+    Next to it a second context replays the scenario closed-loop, reading its own snapshots; its
+    distance from the oracle is reported (and only its bit-exact parts are asserted)."""
+    from concurrent.futures import ThreadPoolExecutor
     from paper_2406_05546_amd.replay import Replay
     theta0 = synth.he_uniform_theta(DATA_SEED)
     o = OracleReplay(sc, DATA_SEED, DROP_SEED, theta0, synth.minibatches, P_DROP, n_threads=n_threads,
                      eval_batch=synth.eval_batch)
     g = Replay(sc, DATA_SEED, DROP_SEED, theta0, P_DROP)
-    stats = {"worst": 0.0, "checked": 0, "tie_workers": 0, "forced": 0}
+    own = Replay(sc, DATA_SEED, DROP_SEED, theta0, P_DROP)          # closed loop, for the record
+    stats = {"worst": 0.0, "worst_elementwise": 0.0, "checked": 0, "images": 0, "tie_workers": 0, "forced": 0,
+             "near_ties": 0, "decisions": 0, "own_grad_apart": 0.0, "own_weights_apart": 0.0, "snapshots": 0,
+             "snapshot_worst": 0.0}
     t0 = time.time()
+    n_grads_events = 0
+    pool = ThreadPoolExecutor(max_workers=min(16, len(os.sched_getaffinity(0))))
     try:
-        for (ev, seqs), (ev_o, seqs_o) in zip(g.steps(), o.steps()):
-            assert ev is ev_o and seqs == seqs_o
+        for (ev, seqs), (ev_o, seqs_o), (ev_c, seqs_c) in zip(g.steps(), o.steps(), own.steps()):
+            assert ev is ev_o and seqs == seqs_o == seqs_c
+            if ev[0] == "snapshot":
+                slot = ev[1]
+                mine = ps.ps_get_weights(g.ctx, slot)
+                assert np.array_equal(mine, ps.ps_get_weights(g.ctx))                  # a publish is a copy
+                errs = parity.assert_close(mine, o.server.ring[slot], parity.WEIGHT_TOL, f"{sc.name} snapshot into slot {slot}")
+                stats["snapshots"] += 1
+                stats["snapshot_worst"] = max(stats["snapshot_worst"], max(errs.values()))
+                ps.ps_load_snapshot(g.ctx, slot, o.server.ring[slot].astype(np.float32), o.server.ring_version[slot])
+                continue
             if ev[0] != "grads":
                 continue
             _, workers, slots, mbs = ev
+            x, y, _, _ = g.last_inputs
+            todo = []
             for i, s in enumerate(seqs):
+                stats["own_grad_apart"] = max(stats["own_grad_apart"], max(parity.rel_errors(own.grad(s), o.last[s].grad).values()))
                 if s % check_every:
                     continue
                 stats["checked"] += 1
+                stats["images"] += sc.batch
                 got = g.grad(s)
-                if parity.is_close(got, o.last[s].grad, parity.GRAD_TOL):
+                if parity.is_close(got, o.last[s].grad, parity.TIE_LOOK):
                     stats["worst"] = max(stats["worst"], max(parity.rel_errors(got, o.last[s].grad).values()))
+                    stats["worst_elementwise"] = max(stats["worst_elementwise"],
+                                                     max(parity.elementwise_errors(got, o.last[s].grad).values()))
+                    assert abs(g.losses[s] - o.losses[s]) <= 2e-5 * abs(o.losses[s])
                 else:
-                    # some max / ReLU sat within rounding reach of a tie: check that the HIP path's
-                    # choice is a valid one and compare against the oracle under that choice
-                    x, y = synth.minibatch(DATA_SEED, mbs[i], sc.batch)
-                    r = parity.check_worker(ps, g.ctx, i, g.entry_of[s], o.server.ring[slots[i]], x, y, mbs[i],
-                                            DROP_SEED, P_DROP, f"{sc.name} gradient seq {s}", tie_tol)
-                    assert r["forced"] > 0, f"{sc.name} gradient seq {s} differs without any tie"
-                    stats["worst"] = max(stats["worst"], r["worst"])
-                    stats["tie_workers"] += 1
-                    stats["forced"] += r["forced"]
-                    # both outcomes of a tie are valid; the oracle's run continues on the branch taken
-                    # so that later steps stay comparable (values are still the oracle's own)
-                    o.last[s].grad[:] = r["grad"]
-                assert abs(g.losses[s] - o.losses[s]) <= 2e-5 * abs(o.losses[s])
+                    # some max / ReLU sat within rounding reach of a tie: check that the HIP path's choice is a
+                    # valid one and compare against the oracle under that choice
+                    todo.append((s, (parity.read_worker(ps, g.ctx, i, grad=got), o.server.ring[slots[i]], x[i], y[i], mbs[i],
+                                     DROP_SEED, P_DROP, f"{sc.name} gradient seq {s}")))
+            for (s, _), r in zip(todo, pool.map(lambda a: parity.judge_worker(*a[1]), todo)):
+                assert abs(g.losses[s] - r["loss"]) <= 2e-5 * abs(r["loss"])
+                stats["worst"] = max(stats["worst"], r["worst"])
+                stats["worst_elementwise"] = max(stats["worst_elementwise"], r["worst_elementwise"])
+                if r["forced"] == 0:
+                    continue                # no decision differs: judge_worker has held it to 1e-4 as it is
+                stats["tie_workers"] += 1
+                stats["forced"] += r["forced"]
+                stats["near_ties"] += r["near_ties"]
+                stats["decisions"] += r["decisions"]
+                # both outcomes of a tie are valid; the oracle's run continues on the branch taken so that
+                # later steps stay comparable (values are still the oracle's own)
+                o.last[s].grad[:] = r["grad"]
+            n_grads_events += 1
+            if progress_every and n_grads_events % progress_every == 0:
+                stats["own_weights_apart"] = max(parity.rel_errors(own.weights(), o.server.theta).values())
+                say(f"{sc.name}: step {n_grads_events}, mean loss {np.mean([o.losses[s] for s in seqs]):.4f}, worst rel err so far "
+                    f"{stats['worst']:.2e}, {stats['tie_workers']} gradients with tie departures; closed-loop run: gradients apart by "
+                    f"up to {stats['own_grad_apart']:.2e}, weights by {stats['own_weights_apart']:.2e}; {time.time() - t0:.0f} s")
         theta_gpu, theta_ref = g.weights(), o.server.theta
-        assert g.dropped == o.dropped and len(g.evals) == len(o.evals)
+        assert g.dropped == o.dropped == own.dropped and len(g.evals) == len(o.evals)
         for (gid, gl, ga, gp), (oid, ol, oa, op, oz) in zip(g.evals, o.evals):
             zs = np.sort(oz, axis=1)
-            clear = (zs[:, -1] - zs[:, -2]) > 1e-4
+            clear = (zs[:, -1] - zs[:, -2]) > 2.0 * parity.REACH[4] * np.abs(oz).max()
             assert gid == oid and abs(gl - ol) <= 2e-5 * abs(ol) and np.array_equal(gp[clear], op[clear])
             assert abs(ga - oa) <= float(np.mean(~clear)) + 1e-12
-        assert g.meta_log == o.meta_log, f"{sc.name}: queue metadata / arrival order differs"
-        assert ps.ps_queue_meta(g.ctx) == [] and ps.ps_version(g.ctx) == o.server.version
+        assert g.meta_log == o.meta_log == own.meta_log, f"{sc.name}: queue metadata / arrival order differs"
+        assert ps.ps_queue_meta(g.ctx) == [] and ps.ps_version(g.ctx) == o.server.version == ps.ps_version(own.ctx)
         errs = parity.assert_close(theta_gpu, theta_ref, parity.WEIGHT_TOL, f"{sc.name} final weights")
+        theta_own = own.weights()
+        assert np.isfinite(theta_own).all()
+        stats["own_weights_apart"] = max(parity.rel_errors(theta_own, theta_ref).values())
         moved = np.linalg.norm(theta_ref - theta0) / np.linalg.norm(theta0)
-        say(f"{sc.name}: {sc.n_gradients} gradients, {stats['checked']} checked, worst rel err {stats['worst']:.2e}, "
-            f"{stats['tie_workers']} with tie departures ({stats['forced']} decisions); weights rel err "
-            f"{max(errs.values()):.2e}; weights moved {moved:.2e}; {time.time() - t0:.1f} s, "
-            f"{o.server.threads_used} oracle threads")
-        assert moved > 1e-4 and stats["tie_workers"] <= max(2, stats["checked"] // 4)
+        say(f"{sc.name}: {sc.n_gradients} gradients, {stats['checked']} checked, worst rel err {stats['worst']:.2e} "
+            f"(elementwise {stats['worst_elementwise']:.2e}), {stats['tie_workers']} with tie departures "
+            f"({stats['forced']} decisions forced out of {stats['near_ties']} inside the rounding reach, "
+            f"{stats['decisions']} decisions in those gradients); {stats['snapshots']} published snapshots rel err up to "
+            f"{stats['snapshot_worst']:.2e}; final weights rel err {max(errs.values()):.2e} (elementwise "
+            f"{max(parity.elementwise_errors(theta_gpu, theta_ref).values()):.2e}); weights moved {moved:.2e}; closed-loop run: "
+            f"gradients apart by up to {stats['own_grad_apart']:.2e}, final weights by {stats['own_weights_apart']:.2e}; "
+            f"{time.time() - t0:.1f} s, {o.server.threads_used} oracle threads")
+        # decisions forced: 0.3 to 1.6 per thousand images on the runs recorded with the profiler summaries
+        assert moved > 1e-4 and stats["forced"] <= max(2, 5e-3 * stats["images"])
         # the difference from the oracle is far below the distance travelled
         assert np.linalg.norm(theta_gpu - theta_ref) <= 2e-3 * np.linalg.norm(theta_ref - theta0)
+        return stats
     finally:
+        pool.shutdown()
+        own.close()
         g.close()
 
 
@@ -208,9 +269,10 @@ def test_config_outage_w8_b64(ps):
     _replay_both(ps, synth.paper_configs()["outage_w8_b64"])
 
 
-def test_config_versions_w64_b128_two_steps(ps):
-    """Eight resident versions, 64 workers per call; two of the 50 steps keep the oracle within seconds."""
-    _replay_both(ps, synth.scenario_versions(64, 128, 8, 2, 0.01))
+def test_config_versions_w64_b128(ps):
+    """Eight resident versions, 64 workers per call, all 50 asynchronous steps: every one of the 3,200
+    gradients, the versions used and the weights after the last step."""
+    _replay_both(ps, synth.paper_configs()["versions_w64_b128"], progress_every=5)
 
 
 def test_outage_recovery_with_backlog_lr_and_clipping(ps):
@@ -240,7 +302,7 @@ def test_evaluate_full_size_and_slots(ps):
         sample = np.r_[0:64, 30000:30064, W * B - 64:W * B]
         l_ref, _, p_ref, z_ref = orc.evaluate(orc.Dims(), theta0.astype(np.float64), x[sample], y[sample])
         zs = np.sort(z_ref, axis=1)
-        clear = (zs[:, -1] - zs[:, -2]) > 1e-4
+        clear = (zs[:, -1] - zs[:, -2]) > 2.0 * parity.REACH[4] * np.abs(z_ref).max()
         assert np.array_equal(pred[sample][clear], p_ref[clear]) and clear.mean() > 0.99
         assert abs(acc - float(np.mean(pred == y))) < 1e-12 and 0.05 < acc < 0.15        # random labels
         assert abs(loss - l_ref) < 0.1 and np.isfinite(loss)
@@ -266,29 +328,117 @@ def test_evaluate_full_size_and_slots(ps):
 
 # ------------------------------------------------------------------ full-size checks
 
-def test_full_size_round_sampled_workers(ps):
-    """W=256, B=256 in one call (the launch configuration the bench times); the oracle checks a
-    sample of workers one by one."""
-    import torch
-    W, B = 256, 256
+def _full_size_multislot_context(ps, W, B, V, capacity):
+    """Context with V distinct snapshots resident: slot v holds the weights after v + 1 asynchronous
+    updates with stand-in gradient rows.  Returns (ctx, the oracle's fp64 copy of every slot)."""
     theta0 = synth.he_uniform_theta(DATA_SEED)
+    ctx = ps.ps_init(ps.make_config(W, B, V, capacity, DROP_SEED, P_DROP))
+    ps.ps_set_weights(ctx, theta0)
+    ref, ring = theta0.astype(np.float64), []
+    rows = synth.gradient_rows(41, 0, V, ps.P, scale=2e-3)
+    for v in range(V):
+        ps.ps_apply_async(ctx, ps.ps_queue_push_host(ctx, rows[v], 0, v, v), 1.0)
+        assert ps.ps_snapshot_weights(ctx, v) == v + 1
+        ref = orc.apply_async(ref, rows[v], 1.0)
+        ring.append(ref)
+    return ctx, ring
+
+
+SAMPLED_WORKERS = (0, 1, 34, 67, 100, 133, 166, 199, 254, 255)      # w % 8 covers every slot; both ends of the grid
+
+
+def test_full_size_round_sampled_workers_on_eight_versions(ps):
+    """W=256, B=256 in one call (the launch configuration the bench times) with eight different
+    snapshots resident, worker w on slot w % 8; the oracle checks ten workers one by one, covering
+    every slot.  Also measures the fp32 rounding of every layer's outputs, which the tie allowance of
+    all parity tests is stated in: the largest |fp32 - fp64| relative to the layer's largest
+    pre-activation must stay below half the allowance."""
+    import torch
+    W, B, V = 256, 256, 8
     mbs = [synth.minibatch_id(w, 0) for w in range(W)]
     x, y = synth.minibatches(DATA_SEED, mbs, B)
-    ctx = ps.ps_init(ps.make_config(W, B, 1, W, DROP_SEED, P_DROP))
+    ctx, ring = _full_size_multislot_context(ps, W, B, V, W)
     try:
-        ps.ps_set_weights(ctx, theta0)
         xd, yd = _torch_inputs(x, y)
         loss = torch.zeros(W, device="cuda")
-        say("full_size: launching W=256 B=256")
-        entries = ps.worker_grads_batched(ctx, range(W), [0] * W, mbs, xd, yd, loss)
+        slots = [w % V for w in range(W)]
+        say("full_size: launching W=256 B=256 on 8 versions")
+        entries = ps.worker_grads_batched(ctx, range(W), slots, mbs, xd, yd, loss)
         ps.ps_sync(ctx)
+        meta = ps.ps_queue_meta(ctx)
+        assert [(m[1], m[2], m[3]) for m in meta] == [(w, w % V + 1, mbs[w]) for w in range(W)]
         losses = loss.cpu().numpy()
         assert np.isfinite(losses).all()
-        for w in (0, 101, 255):
-            r = parity.check_worker(ps, ctx, w, entries[w], theta0.astype(np.float64), x[w], y[w], mbs[w], DROP_SEED,
-                                    P_DROP, f"worker {w}")
+        worst = {1: 0.0, 2: 0.0, 3: 0.0, 4: 0.0}
+        ties = decisions = forced = 0
+        for w in SAMPLED_WORKERS:
+            r = parity.check_worker(ps, ctx, w, entries[w], ring[slots[w]], x[w], y[w], mbs[w], DROP_SEED, P_DROP, f"worker {w}")
             assert abs(losses[w] - r["loss"]) <= 2e-5 * abs(r["loss"])
-            say(f"full_size: worker {w} rel err {r['worst']:.2e}, near-ties {r['near_ties']}, forced {r['forced']}")
+            keep = orc.dropout_keep(DROP_SEED, mbs[w], B, 512, P_DROP)
+            _, _, rec = orc.worker_grad(orc.Dims(), ring[slots[w]], x[w], y[w], keep, P_DROP, records=True)
+            rd = parity.rounding(ps.ps_debug_last_batch(ctx, w), ps.ps_debug_last_activations(ctx, w), rec, keep, P_DROP)
+            for k in worst:
+                worst[k] = max(worst[k], rd[k])
+            ties, decisions, forced = ties + r["near_ties"], decisions + r["decisions"], forced + r["forced"]
+            say(f"full_size: worker {w} slot {slots[w]} rel err {r['worst']:.2e} (elementwise {r['worst_elementwise']:.2e}), "
+                f"near-ties {r['near_ties']}, forced {r['forced']}; rounding / scale conv1 {rd[1]:.2e} conv2 {rd[2]:.2e} "
+                f"fc1 {rd[3]:.2e} fc2 {rd[4]:.2e}; scales {rd['scale'][1]:.2f} {rd['scale'][2]:.2f} {rd['scale'][3]:.2f} {rd['scale'][4]:.2f}")
+        say(f"full_size: largest rounding relative to the layer scale {worst}; {ties} of {decisions} decisions inside the reach, "
+            f"{forced} forced")
+        for k in worst:
+            assert worst[k] * parity.REACH_SAFETY <= parity.REACH[k], f"layer {k}: measured rounding {worst[k]:.2e} is above half the allowance"
+        # an allowance far above the measured rounding would show up as many decisions inside it
+        assert ties <= 3e-5 * decisions
+    finally:
+        ps.ps_destroy(ctx)
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_full_size_drain_on_produced_buffer(ps, mode):
+    """The large outage: four W=256, B=256 rounds on one snapshot leave 1024 buffered gradients
+    (3.3 GB).  Every buffered row is copied to the host and the drain rule is applied to those rows in
+    fp64, as one summed update or as 1024 successive updates; the drained weights must match."""
+    W, B, ROUNDS, lr = 256, 256, 4, 0.005
+    sc = synth.paper_configs()["outage_w256_b256"]
+    assert (sc.n_workers, sc.batch, sc.queue_capacity) == (W, B, W * ROUNDS)
+    theta0 = synth.he_uniform_theta(DATA_SEED)
+    ctx = ps.ps_init(ps.make_config(W, B, 1, W * ROUNDS, DROP_SEED, P_DROP))
+    try:
+        ps.ps_set_weights(ctx, theta0)
+        entries = []
+        for r in range(ROUNDS):
+            mbs = [synth.minibatch_id(w, r) for w in range(W)]
+            x, y = synth.minibatches(DATA_SEED, mbs, B)
+            xd, yd = _torch_inputs(x, y)
+            say(f"produced_buffer: round {r}")
+            entries += ps.worker_grads_batched(ctx, range(W), [0] * W, mbs, xd, yd)
+            ps.ps_sync(ctx)
+        meta = ps.ps_queue_meta(ctx)
+        assert [m[4] for m in meta] == entries and [m[0] for m in meta] == list(range(W * ROUNDS))
+        ref = theta0.astype(np.float64)
+        total = np.zeros_like(ref)
+        norms = []
+        for k, q in enumerate(entries):                      # arrival order
+            row = ps.ps_get_grad(ctx, q)
+            norms.append(float(np.linalg.norm(row)))
+            if mode == 0:
+                total += row
+            else:
+                ref = orc.apply_async(ref, row, lr)
+            if k % 256 == 255:
+                say(f"produced_buffer: {k + 1} rows applied on the host")
+        if mode == 0:
+            ref = orc.apply_async(ref, total, lr)
+        assert np.isfinite(norms).all() and min(norms) > 0
+        assert ps.ps_drain_buffered(ctx, mode, lr) == W * ROUNDS
+        got = ps.ps_get_weights(ctx)
+        errs = parity.assert_close(got, ref, parity.WEIGHT_TOL, "weights after draining the produced buffer")
+        moved = np.abs(ref - theta0).max()
+        say(f"produced_buffer: mode {mode} weights rel err {max(errs.values()):.2e} (elementwise "
+            f"{max(parity.elementwise_errors(got, ref).values()):.2e}); largest move {moved:.2e}, largest difference "
+            f"{np.abs(got - ref).max():.2e}; gradient norms {min(norms):.2f} .. {max(norms):.2f}")
+        assert np.abs(got - ref).max() <= 1e-3 * moved
+        assert ps.ps_version(ctx) == (1 if mode == 0 else W * ROUNDS) and ps.ps_queue_meta(ctx) == []
     finally:
         ps.ps_destroy(ctx)
 
@@ -427,7 +577,7 @@ def test_adadelta_recovery_small_with_carried_state(ps):
                 entries = ps.worker_grads_batched(ctx, range(W), [0] * W, mbs, xd, yd)
                 ref = o.worker_grads_batched(range(W), [0] * W, mbs, x, y)
                 for i in range(W):
-                    if not parity.is_close(ps.ps_get_grad(ctx, entries[i]), ref[i].grad, parity.GRAD_TOL):
+                    if not parity.is_close(ps.ps_get_grad(ctx, entries[i]), ref[i].grad, parity.TIE_LOOK):
                         ref[i].grad[:] = parity.check_worker(ps, ctx, i, entries[i], o.ring[0], x[i], y[i], mbs[i], DROP_SEED,
                                                              P_DROP, f"step {step} worker {i}")["grad"]
                 step += 1
@@ -503,7 +653,7 @@ def test_elastic_averaging_with_worker_local_weights(ps):
                 entries = ps.worker_grads_batched(ctx, range(W), slots, mbs, xd, yd)
                 ref = o.worker_grads_batched(range(W), slots, mbs, x, y)
                 for i in range(W):
-                    if not parity.is_close(ps.ps_get_grad(ctx, entries[i]), ref[i].grad, parity.GRAD_TOL):
+                    if not parity.is_close(ps.ps_get_grad(ctx, entries[i]), ref[i].grad, parity.TIE_LOOK):
                         ref[i].grad[:] = parity.check_worker(ps, ctx, i, entries[i], o.ring[i], x[i], y[i], mbs[i], DROP_SEED,
                                                              P_DROP, f"step {step} worker {i}")["grad"]
                 ps.ps_apply_local(ctx, slots, entries, lr)

@@ -77,7 +77,7 @@ def test_store_in_lockstep_with_the_oracle_over_a_wrapping_queue(ps):
                 g, wk, ver, mb = ps.ps_store_entry(ctx, W * r + i)
                 assert (wk, ver, mb) == (workers[i], ref[i].version, mbs[i])
                 assert abs(losses[i] - ref[i].loss) <= 2e-5 * abs(ref[i].loss)
-                if not parity.is_close(g, ref[i].grad, parity.GRAD_TOL):
+                if not parity.is_close(g, ref[i].grad, parity.TIE_LOOK):
                     res = parity.check_worker(ps, ctx, i, -1, o.ring[slot], x[i], y[i], mbs[i], DROP_SEED, P_DROP,
                                               f"round {r} worker {i}", grad=g)
                     ref[i].grad[:] = res["grad"]            # the oracle goes on from the branch taken
@@ -93,7 +93,7 @@ def test_store_in_lockstep_with_the_oracle_over_a_wrapping_queue(ps):
                 gl, ga, gp = ps.ps_evaluate(ctx, -1, exd, eyd)
                 ol, oa, op, oz = orc.evaluate(orc.Dims(), o.theta, ex, ey)
                 zs = np.sort(oz, axis=1)
-                clear = (zs[:, -1] - zs[:, -2]) > 1e-4
+                clear = (zs[:, -1] - zs[:, -2]) > 2.0 * parity.REACH[4] * np.abs(oz).max()
                 assert abs(gl - ol) <= 2e-5 * abs(ol) and np.array_equal(gp[clear], op[clear])
             parity.assert_close(ps.ps_get_weights(ctx), o.theta, parity.WEIGHT_TOL, f"weights after round {r}")
             parity.assert_close(ps.ps_get_weights(ctx, 1 - slot), o.ring[1 - slot], parity.WEIGHT_TOL, "published slot")
@@ -143,7 +143,7 @@ def test_store_limits_capacity_and_hand_over_to_the_ordered_calls(ps):
         assert ps.ps_store_entry(ctx, 2, want_grad=False)[1:] == (2, 1, mbs[2])      # snapshot version 1
         for i in range(W):
             g = ps.ps_store_entry(ctx, i)[0]
-            if not parity.is_close(g, ref[i].grad, parity.GRAD_TOL):
+            if not parity.is_close(g, ref[i].grad, parity.TIE_LOOK):
                 ref[i].grad[:] = parity.check_worker(ps, ctx, i, -1, o.ring[0], x[i], y[i], mbs[i], DROP_SEED, P_DROP,
                                                      f"worker {i}", grad=g)["grad"]
         with pytest.raises(ps.PsError) as e:
@@ -182,6 +182,40 @@ def test_store_limits_capacity_and_hand_over_to_the_ordered_calls(ps):
             with pytest.raises((ps.PsError, AssertionError)) as e:
                 bad()
             assert not isinstance(e.value, ps.PsError) or e.value.status == ps.PS_EINVAL
+    finally:
+        ps.ps_destroy(ctx)
+
+
+def test_versions_come_back_from_the_store_without_reading_its_state(ps):
+    """Store calls, then ordered calls with nothing but ps_sync in between (no ps_store_state): the
+    update count and the snapshot versions the device kept must be what the ordered calls continue from,
+    and a second store session must start from the ordered calls' count."""
+    W, B, lr = 3, 8, 0.05
+    theta0 = synth.he_uniform_theta(6)
+    mbs = [synth.minibatch_id(w, 0) for w in range(W)]
+    x, y = synth.minibatches(DATA_SEED, mbs, B)
+    xd, yd = _dev(x, y)
+    ctx = ps.ps_init(ps.make_config(W, B, 2, W, DROP_SEED, P_DROP))
+    try:
+        ps.ps_set_weights(ctx, theta0)
+        ps.worker_grads_append(ctx, range(W), [0] * W, mbs, xd, yd)
+        ps.ps_store_consume(ctx, ps.DRAIN_SEQ, lr, 0, True)            # version 3 on the device
+        ps.ps_store_publish(ctx, 1)                                    # slot 1 holds version 3
+        ps.ps_sync(ctx)
+        assert ps.ps_snapshot_weights(ctx, 0) == W                     # first ordered call: no ps_store_state before it
+        assert ps.ps_version(ctx) == W
+        q = ps.worker_grads_batched(ctx, [0, 1], [0, 1], mbs[:2], xd, yd)
+        assert [(m[1], m[2]) for m in ps.ps_queue_meta(ctx)] == [(0, W), (1, W)]   # both snapshots carry version 3
+        ps.ps_apply_sync(ctx, q, lr)
+        assert ps.ps_version(ctx) == W + 1
+        # and the other way round without a read in between
+        ps.worker_grads_append(ctx, [2], [1], mbs[2:], xd[2:].contiguous(), yd[2:].contiguous())
+        ps.ps_store_consume(ctx, ps.DRAIN_SUM, lr, 0, True)
+        assert ps.ps_version(ctx) == W + 2                              # waits for both streams, reads the device count
+        ps.ps_sync(ctx)
+        assert ps.ps_restore_weights(ctx, 1) == 0 and ps.ps_version(ctx) == W
+        st = ps.ps_store_state(ctx)
+        assert (st["claimed"], st["consumed"]) == (W + 1, W + 1)
     finally:
         ps.ps_destroy(ctx)
 
