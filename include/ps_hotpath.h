@@ -55,6 +55,8 @@ extern "C" {
 #define PS_FC1_UNITS 512
 #define PS_POOL1_SIZE 3136 /* 16 x 14 x 14 */
 #define PS_POOL2_SIZE 1568 /* 32 x 7 x 7   */
+#define PS_ROW_FLOATS 813312 /* pitch, in floats, of every P-vector row in device memory: P rounded up to 256 B */
+#define PS_STATIC_DRAIN_MAX_ROWS 4096 /* most rows one ps_drain_rows_mitigated call takes */
 
 typedef struct ps_ctx ps_ctx;
 
@@ -157,6 +159,25 @@ typedef struct {
 } ps_drain_policy;
 PS_API ps_status ps_drain_buffered_mitigated(ps_ctx* ctx, int32_t mode, const ps_drain_policy* policy,
                                       int32_t* n_applied_host, float* lr_used_host);
+
+/* ps_drain_buffered_mitigated for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid allocation.  No context: the
+ * caller owns the weights and the buffered gradients and passes them as rows of PS_ROW_FLOATS floats
+ * (16-byte aligned; the floats beyond PS_PARAM_COUNT in a row are padding and must be zero in the
+ * gradient rows): theta_dev is one row, updated in place; grads_dev holds n_rows rows back to back, in
+ * arrival order.  Mode, policy and *lr_used_host (host, may be NULL) are those of
+ * ps_drain_buffered_mitigated, and the same kernels run, on `hip_stream` (a hipStream_t, NULL for the
+ * default stream), asynchronously.  The row list, the partial sums of the squared norms and the clip
+ * factors, which the context-based call keeps in its workspace, live in a fixed array of 557,056 bytes
+ * in the library's device image (each GPU the process uses holds one copy until the process ends); the
+ * call allocates and frees nothing, on the host or on the device, and clears nothing (every element it
+ * reads it has written first).  n_rows > PS_STATIC_DRAIN_MAX_ROWS gives PS_EINVAL and nothing runs;
+ * n_rows = 0 changes nothing.  All calls on one GPU share that GPU's array: two calls whose kernels may
+ * overlap (different streams, or threads) race.  The address of the array is looked up on the first call
+ * on a device, or by ps_init on that device, whichever comes first; make one of them before a capture
+ * starts.  ps_last_error(NULL) gives the message of the calling thread's last failing call. */
+PS_API ps_status ps_drain_rows_mitigated(float* theta_dev, const float* grads_dev, int32_t n_rows, int32_t mode,
+                                         const ps_drain_policy* policy, float* lr_used_host, void* hip_stream);
 
 /* Recovery with an adaptive learning rate, which Section 2.3 (last paragraph) names, as Adadelta, among
  * the methods for applying the stale gradients; the paper gives no details, so this is the method as
@@ -321,7 +342,8 @@ PS_API ps_status ps_profile_read(ps_ctx* ctx, int32_t kernel_id, double* total_m
 PS_API int32_t ps_profile_kernel_count(void);
 PS_API const char* ps_profile_kernel_name(int32_t kernel_id);
 
-/* Message of the last failing call on this context ("" if none); valid until the next call. */
+/* Message of the last failing call on this context ("" if none); valid until the next call.  With
+ * ctx = NULL: of the calling thread's last failing ps_drain_rows_mitigated call. */
 PS_API const char* ps_last_error(const ps_ctx* ctx);
 
 #ifdef __cplusplus

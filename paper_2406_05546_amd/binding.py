@@ -27,7 +27,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libps_hotpa
 
 EXPORTS = ["ps_workspace_bytes", "ps_init", "ps_destroy", "ps_sync", "ps_set_weights", "ps_get_weights",
            "ps_snapshot_weights", "worker_grads_batched", "ps_queue_push_host", "ps_apply_sync", "ps_apply_async",
-           "ps_drain_buffered", "ps_drain_buffered_mitigated", "ps_drain_buffered_adadelta", "ps_apply_local", "ps_elastic_average", "ps_restore_weights", "ps_load_snapshot", "ps_evaluate",
+           "ps_drain_buffered", "ps_drain_buffered_mitigated", "ps_drain_rows_mitigated", "ps_drain_buffered_adadelta", "ps_apply_local", "ps_elastic_average", "ps_restore_weights", "ps_load_snapshot", "ps_evaluate",
            "worker_grads_append", "ps_store_consume", "ps_store_publish", "ps_store_state", "ps_store_steps",
            "ps_store_entry", "ps_get_grad", "ps_queue_meta", "ps_version", "ps_debug_last_batch", "ps_debug_last_activations", "ps_profile_enable",
            "ps_profile_read", "ps_profile_kernel_count", "ps_profile_kernel_name", "ps_last_error"]
@@ -85,6 +85,7 @@ def load_library() -> ctypes.CDLL:
             "ps_drain_buffered": [vp, i32, f32, ctypes.POINTER(i32)],
             "ps_drain_buffered_mitigated": [vp, i32, ctypes.POINTER(ps_drain_policy), ctypes.POINTER(i32),
                                             ctypes.POINTER(f32)],
+            "ps_drain_rows_mitigated": [vp, vp, i32, i32, ctypes.POINTER(ps_drain_policy), ctypes.POINTER(f32), vp],
             "ps_drain_buffered_adadelta": [vp, f32, f32, f32, ctypes.POINTER(i32)],
             "ps_apply_local": [vp, i32, vp, vp, f32],
             "ps_elastic_average": [vp, vp, i32, f32],
@@ -257,6 +258,29 @@ def ps_drain_buffered_mitigated(ctx: Context, mode: int, lr: float, lr_backlog_r
     st = load_library().ps_drain_buffered_mitigated(ctx.handle, mode, ctypes.byref(pol), ctypes.byref(k), ctypes.byref(used))
     _check(ctx, "ps_drain_buffered_mitigated", st)
     return int(k.value), float(used.value)
+
+
+ROW_FLOATS = 813312
+STATIC_DRAIN_MAX_ROWS = 4096
+
+
+def ps_drain_rows_mitigated(theta_dev, grads_dev, mode: int, lr: float, lr_backlog_ref: float = 0.0,
+                            clip_norm: float = 0.0, n_rows: Optional[int] = None) -> float:
+    """theta_dev: torch float32 cuda tensor of ROW_FLOATS elements, updated in place; grads_dev: torch float32
+    cuda tensor [n_rows, ROW_FLOATS].  Runs on torch's current stream; returns the learning rate used."""
+    import torch
+    n = int(grads_dev.shape[0]) if n_rows is None else n_rows
+    assert theta_dev.is_cuda and theta_dev.dtype == torch.float32 and theta_dev.is_contiguous() and theta_dev.numel() == ROW_FLOATS
+    assert grads_dev.is_cuda and grads_dev.dtype == torch.float32 and grads_dev.is_contiguous()
+    assert n > STATIC_DRAIN_MAX_ROWS or grads_dev.numel() >= n * ROW_FLOATS       # too many rows: the library refuses
+    pol = ps_drain_policy(lr, lr_backlog_ref, clip_norm)
+    used = ctypes.c_float(0.0)
+    stream = torch.cuda.current_stream(theta_dev.device).cuda_stream
+    st = load_library().ps_drain_rows_mitigated(ctypes.c_void_p(theta_dev.data_ptr()), ctypes.c_void_p(grads_dev.data_ptr()), n, mode,
+                                                ctypes.byref(pol), ctypes.byref(used), ctypes.c_void_p(stream))
+    if st != PS_OK:
+        raise PsError("ps_drain_rows_mitigated", st, (load_library().ps_last_error(None) or b"").decode())
+    return float(used.value)
 
 
 def ps_drain_buffered_adadelta(ctx: Context, lr: float, rho: float, eps: float) -> int:

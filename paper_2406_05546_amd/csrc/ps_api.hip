@@ -369,6 +369,11 @@ ps_status ps_init(ps_ctx** out, const ps_config* cfg, void* workspace_dev, uint6
         e = hipHostMalloc(&c->stage[i].host, c->stage_bytes, hipHostMallocDefault);
         if (e == hipSuccess) e = hipEventCreateWithFlags(&c->stage[i].done, hipEventDisableTiming);
     }
+    // the drain entry point that allocates nothing finds its scratch array resolved on this device
+    if (e == hipSuccess) {
+        unsigned char* unused = nullptr;
+        e = static_scratch(&unused);
+    }
     // Weights, ring, queue (padding included) and the index arrays start at zero.
     if (e == hipSuccess) e = hipMemsetAsync(c->ws, 0, lay.p1, c->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
@@ -996,6 +1001,6 @@ int32_t ps_profile_kernel_count(void) { return K_COUNT; }
 
 const char* ps_profile_kernel_name(int32_t kernel_id) { return kernel_name(kernel_id); }
 
-const char* ps_last_error(const ps_ctx* c) { return c ? c->err.c_str() : ""; }
+const char* ps_last_error(const ps_ctx* c) { return c ? c->err.c_str() : static_last_error(); }
 
 }  // extern "C"

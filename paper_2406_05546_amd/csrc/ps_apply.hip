@@ -2,7 +2,19 @@
 // rules; Section 2.3 and the Section 3.3 server pseudo-code for the drain).  One pass over HBM:
 // every buffered gradient is read exactly once, the weights are read and written once and stay
 // in registers while the K gradients stream past, so the SUM and SEQ forms move the same bytes.
+#include "../../include/ps_hotpath.h"
+
+#include <cstdio>
 #include "ps_common.h"
+
+static_assert(PS_ROW_FLOATS == ps::PSTRIDE, "header and kernels disagree on the row pitch");
+
+// Fixed scratch memory of the drain entry point that allocates nothing (ps_drain_rows_mitigated, at the
+// end of this file): row list int32 [rows] | clip factors float [rows] | partial sums of the squared
+// norms float [rows][32].  Every GPU the process uses holds its own copy at its own address; in host
+// code this name is only a handle for hipGetSymbolAddress, never a device address.
+#define PS_STATIC_SCRATCH_BYTES ((size_t)PS_STATIC_DRAIN_MAX_ROWS * (4 + 4 + 4 * 32))  /* 557,056 */
+static __device__ __align__(256) unsigned char scratch[PS_STATIC_SCRATCH_BYTES];
 
 namespace ps {
 
@@ -278,4 +290,90 @@ hipError_t launch_elastic_average(float* theta, float* ring, const int32_t* slot
 
 int norm_slices() { return NORM_SLICES; }
 
+// ---------------------------------------------------------------------------------------------
+// Drain for callers that cannot allocate.  What the context's workspace holds for the mitigated drain
+// (the row list, the per-slice partial sums of the squared norms, the clip factors) lives here in a
+// fixed array in device memory instead; every GPU of the process has its own copy at its own address.
+namespace {
+
+constexpr int STATIC_MAX_ROWS = PS_STATIC_DRAIN_MAX_ROWS;
+constexpr size_t STATIC_IDX_OFF = 0;                                                   // int32 [rows]
+constexpr size_t STATIC_SCALE_OFF = STATIC_IDX_OFF + sizeof(int32_t) * STATIC_MAX_ROWS;  // float [rows]
+constexpr size_t STATIC_PART_OFF = STATIC_SCALE_OFF + sizeof(float) * STATIC_MAX_ROWS;   // float [rows][NORM_SLICES]
+static_assert(STATIC_PART_OFF + sizeof(float) * STATIC_MAX_ROWS * NORM_SLICES == PS_STATIC_SCRATCH_BYTES, "scratch array size");
+
+constexpr int MAX_DEVICES = 64;
+unsigned char* scratch_of_device[MAX_DEVICES] = {};  // device address of `scratch` on each GPU, once resolved
+
+// rows are taken in the order they lie in memory: idx[k] = k
+__global__ __launch_bounds__(256) void row_list_kernel(int32_t* __restrict__ idx, int n)
+{
+    const int k = blockIdx.x * 256 + threadIdx.x;
+    if (k < n) idx[k] = k;
+}
+
+thread_local char static_error[160] = "";
+
+ps_status static_fail(ps_status st, const char* msg)
+{
+    std::snprintf(static_error, sizeof(static_error), "%s", msg);
+    return st;
+}
+
+}  // namespace
+
+// Device address of this GPU's copy of the array (the array's name is only a host-side handle), looked
+// up once per device with that device current.
+hipError_t static_scratch(unsigned char** out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+    if (!scratch_of_device[dev]) {
+        unsigned char* ptr = nullptr;
+        e = hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        scratch_of_device[dev] = ptr;
+    }
+    *out = scratch_of_device[dev];
+    return hipSuccess;
+}
+
+const char* static_last_error() { return static_error; }
+
 }  // namespace ps
+
+extern "C" ps_status ps_drain_rows_mitigated(float* theta_dev, const float* grads_dev, int32_t n_rows, int32_t mode,
+                                             const ps_drain_policy* pol, float* lr_used_host, void* hip_stream)
+{
+    using namespace ps;
+    if (!pol || (mode != PS_DRAIN_SUM && mode != PS_DRAIN_SEQ) || !(pol->lr_backlog_ref >= 0.f) || !(pol->clip_norm >= 0.f))
+        return static_fail(PS_EINVAL, "ps_drain_rows_mitigated: bad mode or policy");
+    if (n_rows < 0) return static_fail(PS_EINVAL, "ps_drain_rows_mitigated: negative row count");
+    if (n_rows > STATIC_MAX_ROWS)
+        return static_fail(PS_EINVAL, "ps_drain_rows_mitigated: more than PS_STATIC_DRAIN_MAX_ROWS (4096) rows");
+    const float K = (float)n_rows;
+    const float lr = (pol->lr_backlog_ref > 0.f && K > pol->lr_backlog_ref) ? pol->lr * (pol->lr_backlog_ref / K) : pol->lr;
+    if (lr_used_host) *lr_used_host = lr;
+    if (n_rows == 0) return PS_OK;
+    if (!theta_dev || !grads_dev || (reinterpret_cast<uintptr_t>(theta_dev) & 15) || (reinterpret_cast<uintptr_t>(grads_dev) & 15))
+        return static_fail(PS_EINVAL, "ps_drain_rows_mitigated: null or misaligned device pointer");
+    unsigned char* base = nullptr;
+    if (static_scratch(&base) != hipSuccess)
+        return static_fail(PS_EDEVICE, "ps_drain_rows_mitigated: the address of the static scratch array could not be resolved");
+    int32_t* idx = reinterpret_cast<int32_t*>(base + STATIC_IDX_OFF);
+    float* scale = reinterpret_cast<float*>(base + STATIC_SCALE_OFF);
+    float* partial = reinterpret_cast<float*>(base + STATIC_PART_OFF);
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    static Profiler no_timing;  // never enabled
+    // Nothing in the array has to start at zero: the row list, every partial sum and every clip factor of
+    // the rows in use are written before they are read.
+    hipLaunchKernelGGL(row_list_kernel, dim3((n_rows + 255) / 256), dim3(256), 0, s, idx, (int)n_rows);
+    hipError_t e = pol->clip_norm > 0.f
+                       ? launch_apply_clipped(theta_dev, grads_dev, idx, n_rows, lr, mode, pol->clip_norm, partial, scale, s, no_timing)
+                       : launch_apply(theta_dev, grads_dev, idx, n_rows, lr, mode, s, no_timing);
+    if (e != hipSuccess) return static_fail(PS_EDEVICE, hipGetErrorString(e));
+    return PS_OK;
+}

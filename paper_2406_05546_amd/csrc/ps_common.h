@@ -140,6 +140,11 @@ hipError_t launch_apply_clipped(float* theta, const float* queue, const int32_t*
                                 float clip, float* partial_dev, float* scale_dev, hipStream_t s, Profiler& prof);
 int norm_slices();
 
+// Device address, on the current GPU, of the library's fixed scratch array (used by the drain entry point
+// that allocates nothing); resolved on first use per device.
+hipError_t static_scratch(unsigned char** out);
+const char* static_last_error();
+
 // ring[slot_j] -= lr * queue[q_j] for n (slot, q) pairs with distinct slots (pairs_dev: 2n int32).
 hipError_t launch_local_steps(float* ring, const float* queue, const int32_t* pairs_dev, int n, float lr, hipStream_t s,
                               Profiler& prof);

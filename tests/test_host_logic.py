@@ -15,7 +15,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "ps_hotpath.h")).read()
     declared = re.findall(r"^PS_API\s+[\w\s\*]+?\b(\w+)\(", header, flags=re.M)
-    assert sorted(declared) == sorted(ps.EXPORTS) and len(declared) == 35
+    assert sorted(declared) == sorted(ps.EXPORTS) and len(declared) == 36
     lib = ps.load_library()
     for name in declared:
         assert getattr(lib, name) is not None
@@ -121,3 +121,4 @@ def test_loading_the_library_brings_in_torch_first():
             "binding.load_library(); assert 'torch' in sys.modules; print('ok')")
     out = subprocess.run([sys.executable, "-c", code], cwd=ROOT, capture_output=True, text=True, timeout=300)
     assert out.returncode == 0 and out.stdout.strip().endswith("ok"), out.stderr[-2000:]
+
