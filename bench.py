@@ -8,9 +8,14 @@ the backlog (odd steps as one summed update, even steps as 1024 successive updat
 weights are published with ps_snapshot_weights.  Inputs are synthetic, seeded, and resident in HBM
 before the timed region.
 
-Prints ONE JSON line: whole-step images/s, plus the roofline of the dominant kernel (timed live
-with HIP events on the library's stream), the drain's HBM roofline, a per-kernel table, and the CPU
-oracle timed on a bounded sample as a baseline.
+Three passes over the same K steps: (1) the whole step, nothing but the library's own launches on
+the stream -> `value`; (2) the same steps with HIP events around the four worker rounds and around
+the drain -> worker-only images/s and drain GB/s; (3) the same steps with the library's per-kernel
+HIP events on -> the per-kernel table and the roofline of the dominant kernel.  Then the second
+timed configuration (W = 64, B = 128, eight resident versions, 50 asynchronous steps), and the
+variants of the drain, each outside the passes above.
+
+Prints ONE JSON line.
 """
 import argparse
 import json
@@ -54,14 +59,14 @@ REDUCE_BYTES_PER_WORKER = (32 * 4640 + 32 * 160 + 2 * 5643 + 4800 + 5643) * 4
 # that changes afterwards must be set to None here until its counters are taken again.
 MIB = 1 << 20
 MEASURED_HBM_BYTES = {
-    "conv1_fwd_kernel": (196.9 + 1013.7) * MIB, "conv2_fwd_kernel": (785.1 + 494.7) * MIB,
+    "conv1_fwd_kernel": (196.9 + 1014.0) * MIB, "conv2_fwd_kernel": (785.1 + 494.7) * MIB,
     "gemm_f32_mfma<Fc1FwdEpi>": (578.5 + 130.9) * MIB, "fc2_kernel": (128.6 + 141.8) * MIB,
     # weight / input gradient: one launch each, wide tiles plus narrow tiles for the feature edge
-    "gemm_f32_mfma<Fc1DwEpi>": (659.4 + 784.0) * MIB,
-    "gemm_f32_mfma<Fc1DxEpi>": (940.7 + 392.3) * MIB,
+    "gemm_f32_mfma<Fc1DwEpi>": (659.6 + 784.0) * MIB,
+    "gemm_f32_mfma<Fc1DxEpi>": (940.6 + 392.3) * MIB,
     "conv2_dw_kernel": (1274.1 + 145.0) * MIB, "conv2_dx_kernel": (882.8 + 5.0) * MIB,
     "grad_reduce_kernel": (161.3 + 10.2) * MIB, "apply_kernel<0>": (3180.1 + 3.1) * MIB,
-    "apply_kernel<1>": (3180.1 + 3.1) * MIB, "grad_sqnorm_kernel": (3216.3 + 1.0) * MIB,
+    "apply_kernel<1>": (3180.1 + 3.1) * MIB, "grad_sqnorm_kernel": (3215.3 + 1.0) * MIB,
     "apply_kernel<1, clip>": (3180.1 + 3.1) * MIB, "apply_adadelta_kernel": (3186.3 + 9.3) * MIB,
     "elastic_average_kernel": (797.4 + 797.4) * MIB,
 }
@@ -93,6 +98,94 @@ def cpu_baseline():
             "sample": f"{n} workers x {B} images fwd+bwd in {dt:.1f} s on {used} threads; drain of 64 of 1024 rows "
                       f"x {P} floats in {dd:.2f} s on 1 thread",
             "single_thread_images_per_s": 2 * B / d1, "drain_GBps": (64 * P * 4 + 2 * P * 4) / dd / 1e9}
+
+
+def kernel_table(prof, n_workers, batch, drain_rows):
+    """Per-kernel figures from the library's event timing: achieved rate against the kernel's bound."""
+    n_images = n_workers * batch
+    kernels = []
+    for name, (ms, n) in prof.items():
+        if n == 0:
+            continue
+        avg = ms / n
+        if name in APPLY_KERNELS:
+            algo = drain_rows * P * 4 + 2 * P * 4
+            ach = algo / (avg * 1e-3) / 1e9
+            kernels.append({"kernel": name, "launches": n, "avg_ms": avg, "bound": "hbm", "achieved": ach,
+                            "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBPS, "total_ms": ms})
+        elif name in ("grad_reduce_kernel", "fc2_kernel"):
+            algo = REDUCE_BYTES_PER_WORKER * n_workers if name == "grad_reduce_kernel" else FC2_BYTES_PER_IMAGE * n_images
+            ach = algo / (avg * 1e-3) / 1e9
+            kernels.append({"kernel": name, "launches": n, "avg_ms": avg, "bound": "hbm", "achieved": ach,
+                            "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBPS, "total_ms": ms})
+        elif name in KERNEL_FLOP_PER_IMAGE:
+            flop = KERNEL_FLOP_PER_IMAGE[name] * n_images
+            ach = flop / (avg * 1e-3) / 1e12
+            alu = name in ALU_KERNELS
+            peak = PEAK_VALU_F32_TFLOPS if alu else PEAK_MFMA_F32_TFLOPS
+            kernels.append({"kernel": name, "launches": n, "avg_ms": avg, "bound": "alu" if alu else "mfma", "achieved": ach,
+                            "peak": peak, "unit": "TFLOP/s", "frac": ach / peak, "total_ms": ms})
+    kernels.sort(key=lambda k: -k["total_ms"])
+    return kernels
+
+
+def secondary_config(ps, synth, torch, dev, steps=50, warmup=3):
+    """The second timed configuration: W = 64 workers x B = 128 images, eight weight versions resident and
+    read round-robin (worker w reads slot w % 8), asynchronous steps: a step's 64 gradients are applied one
+    by one in worker order (one kernel: a sequential drain of 64 rows) and the result is published into slot
+    step % 8.  Timed with events around worker_grads_batched only; the apply is timed separately."""
+    import statistics
+    W2, B2, V2, lr = 64, 128, 8, 0.00125
+    ctx = ps.ps_init(ps.make_config(W2, B2, V2, W2, 0xD0D1, 0.25), dev)
+    ps.ps_set_weights(ctx, synth.he_uniform_theta(2))
+    workers, slots = list(range(W2)), [w % V2 for w in range(W2)]
+    x, y = synth.minibatches(2, [synth.minibatch_id(w, 0) for w in workers], B2)
+    xd, yd = torch.from_numpy(x).to(dev), torch.from_numpy(y).to(dev)
+    loss = torch.zeros(W2, device=dev)
+
+    def one(i, events=None):
+        if events:
+            events[0].record()
+        ps.worker_grads_batched(ctx, workers, slots, [synth.minibatch_id(w, i) for w in workers], xd, yd, loss)
+        if events:
+            events[1].record()
+        ps.ps_drain_buffered(ctx, ps.DRAIN_SEQ, lr)
+        if events:
+            events[2].record()
+        ps.ps_snapshot_weights(ctx, i % V2)
+
+    for i in range(warmup + V2):                       # also makes the eight slots eight different versions
+        one(i)
+    ps.ps_sync(ctx)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+    t0 = time.perf_counter()
+    for i in range(steps):
+        one(warmup + V2 + i, ev[i])
+    ps.ps_sync(ctx)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    grads_ms = [e[0].elapsed_time(e[1]) for e in ev]
+    apply_ms = [e[1].elapsed_time(e[2]) for e in ev]
+    ps.ps_profile_enable(ctx, True)
+    for i in range(steps):
+        one(warmup + V2 + steps + i)
+    prof = ps.ps_profile_read(ctx)
+    ps.ps_profile_enable(ctx, False)
+    final_loss = float(loss.mean().item())
+    ps.ps_destroy(ctx)
+    med = statistics.median(grads_ms)
+    kernels = kernel_table(prof, W2, B2, W2)
+    worker_ms = sum(k["total_ms"] for k in kernels if k["kernel"] not in APPLY_KERNELS) / steps
+    tflops = FLOP_PER_IMAGE * W2 * B2 / (med * 1e-3) / 1e12
+    return {"workload": f"versions_w64_b128: W={W2} workers x B={B2} images per step, {V2} weight versions resident, worker w reads "
+                        f"slot w % {V2}; {steps} asynchronous steps (64 applies in arrival order, publish into slot step % {V2})",
+            "metric": "worker gradient images/sec (fwd+bwd), worker_grads_batched only, median over the steps",
+            "value": W2 * B2 / (med * 1e-3), "unit": "images/s", "steps": steps, "median_ms": med,
+            "min_ms": min(grads_ms), "max_ms": max(grads_ms), "achieved_TFLOPs": tflops,
+            "frac_of_fp32_mfma_peak": tflops / PEAK_MFMA_F32_TFLOPS,
+            "kernel_time_sum_ms": worker_ms, "apply_64_sequential_median_ms": statistics.median(apply_ms),
+            "whole_step_ms_wall": wall / steps * 1e3, "final_mean_loss": final_loss,
+            "kernels": [{k: v for k, v in kk.items() if k != "total_ms"} for kk in kernels]}
 
 
 def main():
@@ -141,13 +234,39 @@ def main():
         step(i)
     ps.ps_sync(ctx)
     torch.cuda.synchronize()
-    ps.ps_profile_enable(ctx, True)
+    # pass 1: the whole step, no events of any kind inside
     t0 = time.perf_counter()
     for i in range(args.steps):
         step(args.warmup + i)
     ps.ps_sync(ctx)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+
+    # pass 2: the same steps with events (on the library's stream, which is torch's current one) around the
+    # worker rounds and around the drain
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    for i in range(args.steps):
+        j = args.warmup + args.steps + i
+        ev[i][0].record()
+        for r in range(ROUNDS):
+            ps.worker_grads_batched(ctx, workers, slots, [synth.minibatch_id(w, j * ROUNDS + r) for w in workers], xs[r], ys[r], loss)
+        ev[i][1].record()
+        ev[i][2].record()
+        ps.ps_drain_buffered(ctx, ps.DRAIN_SUM if j % 2 else ps.DRAIN_SEQ, LR)
+        ev[i][3].record()
+        ps.ps_snapshot_weights(ctx, 0)
+    ps.ps_sync(ctx)
+    torch.cuda.synchronize()
+    worker_ms_events = [e[0].elapsed_time(e[1]) for e in ev]
+    drain_ms_events = {"sum": [e[2].elapsed_time(e[3]) for i, e in enumerate(ev) if (args.warmup + args.steps + i) % 2],
+                       "seq": [e[2].elapsed_time(e[3]) for i, e in enumerate(ev) if not (args.warmup + args.steps + i) % 2]}
+
+    # pass 3: the same steps with the library's per-kernel events on
+    ps.ps_profile_enable(ctx, True)
+    for i in range(args.steps):
+        step(args.warmup + 2 * args.steps + i)
+    ps.ps_sync(ctx)
+    torch.cuda.synchronize()
     prof = ps.ps_profile_read(ctx)
     # outside the timed region: one more backlog, drained with learning-rate scaling and norm clipping
     ps.ps_profile_enable(ctx, True)
@@ -215,45 +334,44 @@ def main():
 
     images_per_step = W * B * ROUNDS
     n_launch_images = W * B
-    kernels = []
-    for name, (ms, n) in prof.items():
-        if n == 0:
-            continue
-        avg = ms / n
-        if name in APPLY_KERNELS:
-            algo = W * ROUNDS * P * 4 + 2 * P * 4
-            ach = algo / (avg * 1e-3) / 1e9
-            kernels.append({"kernel": name, "launches": n, "avg_ms": avg, "bound": "hbm", "achieved": ach,
-                            "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBPS, "total_ms": ms})
-        elif name in ("grad_reduce_kernel", "fc2_kernel"):
-            algo = REDUCE_BYTES_PER_WORKER * W if name == "grad_reduce_kernel" else FC2_BYTES_PER_IMAGE * n_launch_images
-            ach = algo / (avg * 1e-3) / 1e9
-            kernels.append({"kernel": name, "launches": n, "avg_ms": avg, "bound": "hbm", "achieved": ach,
-                            "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBPS, "total_ms": ms})
-        else:
-            flop = KERNEL_FLOP_PER_IMAGE[name] * n_launch_images
-            ach = flop / (avg * 1e-3) / 1e12
-            alu = name in ALU_KERNELS
-            peak = PEAK_VALU_F32_TFLOPS if alu else PEAK_MFMA_F32_TFLOPS
-            kernels.append({"kernel": name, "launches": n, "avg_ms": avg, "bound": "alu" if alu else "mfma", "achieved": ach,
-                            "peak": peak, "unit": "TFLOP/s", "frac": ach / peak, "total_ms": ms})
+    kernels = kernel_table(prof, W, B, W * ROUNDS)
     kernels.sort(key=lambda k: -k["total_ms"])
     dom = kernels[0]
     roofline = {k: dom[k] for k in ("bound", "achieved", "peak", "unit", "frac")}
     roofline.update({"kernel": dom["kernel"], "avg_ms": dom["avg_ms"], "traffic": MEASURED_HBM_BYTES.get(dom["kernel"]),
-                     "traffic_unit": "bytes per launch (HBM, measured)"})
+                     "traffic_unit": "HBM bytes per launch from the rocprofv3 counter summary kept with the profiles "
+                                     "(not re-measured by this run)"})
     drains = [k for k in kernels if k["kernel"] in APPLY_KERNELS]
     worker_ms = sum(k["total_ms"] for k in kernels if k["kernel"] not in APPLY_KERNELS)
     worker_tflops = FLOP_PER_IMAGE * images_per_step * args.steps / (worker_ms * 1e-3) / 1e12 if worker_ms else 0.0
 
+    import statistics
+    drain_bytes = W * ROUNDS * P * 4 + 2 * P * 4
+    worker_med_ms = statistics.median(worker_ms_events)
+    worker_events_tflops = FLOP_PER_IMAGE * images_per_step / (worker_med_ms * 1e-3) / 1e12
+    drain_events = {}
+    for mode, ms_list in drain_ms_events.items():
+        if ms_list:
+            m = statistics.median(ms_list)
+            drain_events[mode] = {"median_ms": m, "GBps": drain_bytes / (m * 1e-3) / 1e9,
+                                  "frac_of_hbm_peak": drain_bytes / (m * 1e-3) / 1e9 / PEAK_HBM_GBPS}
+    roofline["timed"] = "pass 3: the same K steps as `value`, with the library's HIP events around every kernel launch"
     out = {
-        "metric": "worker gradient images/sec (fwd+bwd) at 1 GPU, whole step incl. buffered-grad drain",
+        "metric": "worker gradient images/sec (fwd+bwd) at 1 GPU; buffered-grad drain HBM GB/s",
         "value": images_per_step * args.steps / dt, "unit": "images/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "value_is": "whole step: 4 worker rounds + drain of the 1024 buffered gradients + publish, images of the step / wall "
+                    "time, no events inside the timed region (pass 1)",
         "config": {"workload": f"outage_w256_b256: {ROUNDS} rounds x W={W} workers x B={B} images on one snapshot "
                                f"-> {W * ROUNDS} buffered gradients (3.33 GB) -> drain (SUM/SEQ alternating) -> publish",
                    "images_per_step": images_per_step, "lr": LR, "dropout_p": 0.25},
+        # the two parts of the metric on their own (pass 2: events around the four worker rounds and around the drain)
+        "worker_images_per_s": images_per_step / (worker_med_ms * 1e-3),
+        "worker_only": {"median_ms_per_4_rounds": worker_med_ms, "achieved_TFLOPs": worker_events_tflops,
+                        "frac_of_fp32_mfma_peak": worker_events_tflops / PEAK_MFMA_F32_TFLOPS},
+        "drain_GBps": {k: v["GBps"] for k, v in drain_events.items()},
+        "drain_only": dict(drain_events, algorithmic_bytes=drain_bytes),
         "roofline": roofline,
         "worker_kernels_sum": {"achieved": worker_tflops, "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s",
                                "frac": worker_tflops / PEAK_MFMA_F32_TFLOPS,
@@ -292,6 +410,7 @@ def main():
         "ms_per_step": store_ms, "images_per_s": images_per_step / (store_ms * 1e-3),
         "ordered_seq_ms_per_step": ordered_ms, "ordered_seq_images_per_s": images_per_step / (ordered_ms * 1e-3),
         "steps": n_ov}
+    out["secondary"] = secondary_config(ps, synth, torch, dev)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()
     print(json.dumps(out))
