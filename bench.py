@@ -194,6 +194,7 @@ def main():
     ap.add_argument("--steps", type=int, default=8)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--ceilings-only", action="store_true", help="print only the chip ceilings measured on this box")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (workers are a batch dimension); use --gpus 1")
@@ -205,6 +206,12 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     dev = "cuda:0"
+    # what the chip sustains with the same instructions (fp32 MFMAs alone, MFMAs next to vector-ALU work,
+    # plain HBM streams): outside every timed region
+    ceilings = ps.ps_measure_ceilings(dev)
+    if args.ceilings_only:
+        print(json.dumps({"ceilings": ceilings, "published": {"mfma_f32_TFLOPs": PEAK_MFMA_F32_TFLOPS, "hbm_GBps": PEAK_HBM_GBPS}}))
+        return
     ctx = ps.ps_init(ps.make_config(W, B, 2, W * ROUNDS, 0xD0D0, 0.25), dev)
     ps.ps_set_weights(ctx, synth.he_uniform_theta(1))
     xs, ys = [], []
@@ -411,6 +418,14 @@ def main():
         "ordered_seq_ms_per_step": ordered_ms, "ordered_seq_images_per_s": images_per_step / (ordered_ms * 1e-3),
         "steps": n_ov}
     out["secondary"] = secondary_config(ps, synth, torch, dev)
+    # the same fractions against what this chip was measured to sustain (published peaks stay the denominators above)
+    out["ceilings"] = dict(ceilings, note="measured on this box by ps_measure_ceilings before the timed passes")
+    out["roofline"]["frac_of_measured_ceiling"] = (
+        roofline["achieved"] / (ceilings["mfma_16x16x4_tflops"] if roofline["bound"] != "hbm" else ceilings["hbm_read_GBps"]))
+    out["worker_only"]["frac_of_measured_mfma_ceiling"] = worker_events_tflops / ceilings["mfma_32x32x2_tflops"]
+    for mode, v in out["drain_only"].items():
+        if isinstance(v, dict):
+            v["frac_of_measured_hbm_read"] = v["GBps"] / ceilings["hbm_read_GBps"]
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()
     print(json.dumps(out))

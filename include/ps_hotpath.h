@@ -342,6 +342,30 @@ PS_API ps_status ps_profile_read(ps_ctx* ctx, int32_t kernel_id, double* total_m
 PS_API int32_t ps_profile_kernel_count(void);
 PS_API const char* ps_profile_kernel_name(int32_t kernel_id);
 
+/* What the chip sustains with the instructions this library's kernels are made of (instrumentation for
+ * the roofline figures, not part of the method).  Runs short timing kernels on `hip_stream` over the
+ * caller's device buffer (256-byte aligned, at least 64 MiB, up to 4 GiB of it are streamed; its contents
+ * are overwritten) and waits for them:
+ *   mfma_32x32x2_tflops / mfma_16x16x4_tflops   fp32 MFMA rate over all compute units, nothing else issued
+ *                                               (first_launch: before the clock has ramped up under load)
+ *   ns_per_mfma_with_valu[i]                    time per 16x16x4 MFMA of a wavefront that issues 0, 1, 2, 4
+ *                                               independent vector FMAs behind every MFMA (one wavefront per SIMD)
+ *   shared_simd_ms[0..2]                        the same MFMA loop alone, a vector-FMA loop alone, and both as
+ *                                               two wavefronts sharing every SIMD: [2] near max([0], [1]) means
+ *                                               the two kinds overlap, near [0] + [1] that they do not
+ *   hbm_read_GBps / hbm_copy_GBps               one pass of 16-byte loads over the buffer / copy of one half to
+ *                                               the other (bytes read + bytes written) */
+typedef struct {
+    int32_t compute_units;
+    double mfma_32x32x2_tflops, mfma_32x32x2_first_launch_tflops, mfma_16x16x4_tflops;
+    double ns_per_mfma_16x16x4;
+    double ns_per_mfma_with_valu[4];
+    double shared_simd_ms[3];
+    double hbm_read_GBps, hbm_copy_GBps;
+    uint64_t hbm_read_bytes;
+} ps_ceilings;
+PS_API ps_status ps_measure_ceilings(void* workspace_dev, uint64_t workspace_bytes, void* hip_stream, ps_ceilings* out_host);
+
 /* Message of the last failing call on this context ("" if none); valid until the next call.  With
  * ctx = NULL: of the calling thread's last failing ps_drain_rows_mitigated call. */
 PS_API const char* ps_last_error(const ps_ctx* ctx);

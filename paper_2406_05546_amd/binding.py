@@ -30,7 +30,7 @@ EXPORTS = ["ps_workspace_bytes", "ps_init", "ps_destroy", "ps_sync", "ps_set_wei
            "ps_drain_buffered", "ps_drain_buffered_mitigated", "ps_drain_rows_mitigated", "ps_drain_buffered_adadelta", "ps_apply_local", "ps_elastic_average", "ps_restore_weights", "ps_load_snapshot", "ps_evaluate",
            "worker_grads_append", "ps_store_consume", "ps_store_publish", "ps_store_state", "ps_store_steps",
            "ps_store_entry", "ps_get_grad", "ps_queue_meta", "ps_version", "ps_debug_last_batch", "ps_debug_last_activations", "ps_profile_enable",
-           "ps_profile_read", "ps_profile_kernel_count", "ps_profile_kernel_name", "ps_last_error"]
+           "ps_profile_read", "ps_profile_kernel_count", "ps_profile_kernel_name", "ps_measure_ceilings", "ps_last_error"]
 
 
 class PsError(RuntimeError):
@@ -51,6 +51,14 @@ class ps_store_counters(ctypes.Structure):
 class ps_store_step(ctypes.Structure):
     _fields_ = [("first", ctypes.c_uint64), ("count", ctypes.c_uint32), ("mode", ctypes.c_uint32),
                 ("version_after", ctypes.c_uint64)]
+
+
+class ps_ceilings(ctypes.Structure):
+    _fields_ = [("compute_units", ctypes.c_int32), ("mfma_32x32x2_tflops", ctypes.c_double),
+                ("mfma_32x32x2_first_launch_tflops", ctypes.c_double), ("mfma_16x16x4_tflops", ctypes.c_double),
+                ("ns_per_mfma_16x16x4", ctypes.c_double), ("ns_per_mfma_with_valu", ctypes.c_double * 4),
+                ("shared_simd_ms", ctypes.c_double * 3), ("hbm_read_GBps", ctypes.c_double), ("hbm_copy_GBps", ctypes.c_double),
+                ("hbm_read_bytes", ctypes.c_uint64)]
 
 
 class ps_config(ctypes.Structure):
@@ -105,6 +113,7 @@ def load_library() -> ctypes.CDLL:
             "ps_debug_last_activations": [vp, i32, vp, vp, vp, vp],
             "ps_profile_enable": [vp, i32],
             "ps_profile_read": [vp, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)],
+            "ps_measure_ceilings": [vp, u64, vp, ctypes.POINTER(ps_ceilings)],
         }
         for name, args in sig.items():
             fn = getattr(lib, name)
@@ -422,6 +431,24 @@ def ps_debug_last_activations(ctx: Context, i: int) -> dict:
     st = load_library().ps_debug_last_activations(ctx.handle, i, _vp(out["pool1_val"]), _vp(out["pool2_val"]), _vp(out["d3"]),
                                                   _vp(out["dpool2"]))
     _check(ctx, "ps_debug_last_activations", st)
+    return out
+
+
+def ps_measure_ceilings(device: str = "cuda:0", gib: float = 2.0) -> dict:
+    """Chip ceilings measured with short timing kernels on torch's current stream over a torch buffer."""
+    import torch
+    dev = torch.device(device)
+    torch.cuda.set_device(dev)
+    buf = torch.empty(int(gib * (1 << 30)), dtype=torch.uint8, device=dev)
+    c = ps_ceilings()
+    st = load_library().ps_measure_ceilings(ctypes.c_void_p(buf.data_ptr()), buf.numel(),
+                                            ctypes.c_void_p(torch.cuda.current_stream(dev).cuda_stream), ctypes.byref(c))
+    if st != PS_OK:
+        raise PsError("ps_measure_ceilings", st)
+    out = {}
+    for name, _ in ps_ceilings._fields_:
+        v = getattr(c, name)
+        out[name] = list(v) if hasattr(v, "__len__") else v
     return out
 
 

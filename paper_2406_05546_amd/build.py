@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libps_hotpath.so")
 SOURCES = ["ps_api.hip", "ps_apply.hip", "ps_store.hip", "ps_worker.hip", "ps_conv1.hip", "ps_conv2.hip", "ps_fc1.hip",
-           "ps_fc2.hip", "ps_profile.hip"]
+           "ps_fc2.hip", "ps_profile.hip", "ps_ceilings.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fvisibility=hidden",
          # keep the compiler from forming packed-fp32 instructions
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -15,7 +15,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "ps_hotpath.h")).read()
     declared = re.findall(r"^PS_API\s+[\w\s\*]+?\b(\w+)\(", header, flags=re.M)
-    assert sorted(declared) == sorted(ps.EXPORTS) and len(declared) == 36
+    assert sorted(declared) == sorted(ps.EXPORTS) and len(declared) == 37
     lib = ps.load_library()
     for name in declared:
         assert getattr(lib, name) is not None
