@@ -77,40 +77,67 @@ struct Pool1Stage {
 };
 
 // Gated pool2 gradient of COUNT images, routed to the window winners of padded planes
-// d2[o][16][16] (interior at (1,1)).  clear() zeroes exactly the elements the last commit wrote.
+// d2[o][16][16] (interior at (1,1)).  A thread moves four consecutive values at a time (one 16-byte load
+// of gradients, one 4-byte load of window bytes); where a value lands apart from its winner's place in
+// the window never changes, so those offsets are computed once per block (two 16-bit offsets per
+// register) and a commit costs a handful of vector instructions per value instead of the divisions by 49
+// and 7.  Before the next commit the planes are cleared as a whole with 16-byte stores.
 template <int COUNT, int CHS>
 struct D2Stage {
     static constexpr int D2_IMS = C2 * CHS;
-    static constexpr int N = COUNT * P2_SIZE, NV = (N + 255) / 256;
-    float v[NV];
-    uint8_t code[NV];
-    uint16_t at[NV];
+    static constexpr int N4 = COUNT * (P2_SIZE / 4), NV = (N4 + 255) / 256;
+    static_assert(P2_SIZE % 4 == 0, "a group of four values never straddles two images");
+    static_assert(COUNT * D2_IMS < (1 << 16), "offsets must fit 16 bits");
+    floatx4 v[NV];
+    uint32_t code[NV];
+    uint32_t base[NV][2];  // offsets of the four values' windows (winner (0,0)), 16 bits each
+    __device__ __forceinline__ void init(int tid)
+    {
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {
+            uint32_t b[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int e = min(4 * (tid + 256 * k), COUNT * P2_SIZE - 4) + j;
+                const int img = e / P2_SIZE, r = e % P2_SIZE, o = r / P2_POS, p = r % P2_POS;
+                b[j] = (uint32_t)(img * D2_IMS + o * CHS + (2 * (p / P2_W) + 1) * 16 + 2 * (p % P2_W) + 1);
+            }
+            base[k][0] = b[0] | (b[1] << 16);
+            base[k][1] = b[2] | (b[3] << 16);
+        }
+    }
     __device__ __forceinline__ void prefetch(const WorkerBuffers& wb, size_t g0, int valid, int tid)
     {
 #pragma unroll
         for (int k = 0; k < NV; ++k) {
-            const int i = tid + 256 * k;
-            const bool ok = i < N && i / P2_SIZE < valid;
-            v[k] = ok ? wb.dp2g[g0 * P2_SIZE + i] : 0.f;
-            code[k] = ok ? wb.am2[g0 * P2_SIZE + i] : 0;
+            const int i4 = tid + 256 * k;
+            const bool ok = (256 * (k + 1) <= N4 || i4 < N4) && (4 * i4) / P2_SIZE < valid;
+            v[k] = ok ? *reinterpret_cast<const floatx4*>(wb.dp2g + g0 * P2_SIZE + (size_t)i4 * 4) : floatx4{0.f, 0.f, 0.f, 0.f};
+            code[k] = ok ? *reinterpret_cast<const uint32_t*>(wb.am2 + g0 * P2_SIZE + (size_t)i4 * 4) : 0u;
         }
     }
-    __device__ __forceinline__ void commit(float* __restrict__ d2, int tid)
+    __device__ __forceinline__ void commit(float* __restrict__ d2, int tid) const
     {
 #pragma unroll
         for (int k = 0; k < NV; ++k) {
-            const int i = tid + 256 * k;
-            if (i >= N) break;
-            const int img = i / P2_SIZE, r = i % P2_SIZE, o = r / P2_POS, p = r % P2_POS, cd = code[k] & 3;
-            at[k] = (uint16_t)(img * D2_IMS + o * CHS + (2 * (p / P2_W) + (cd >> 1) + 1) * 16 + 2 * (p % P2_W) + (cd & 1) + 1);
-            d2[at[k]] = v[k];
+            if (!(256 * (k + 1) <= N4 || tid + 256 * k < N4)) break;
+            // winner (dy, dx) of every byte -> dy * 16 + dx, four at once
+            const uint32_t off = (code[k] & 0x01010101u) | ((code[k] & 0x02020202u) << 3);
+            d2[(base[k][0] & 0xffffu) + (off & 0xffu)] = v[k][0];
+            d2[(base[k][0] >> 16) + ((off >> 8) & 0xffu)] = v[k][1];
+            d2[(base[k][1] & 0xffffu) + ((off >> 16) & 0xffu)] = v[k][2];
+            d2[(base[k][1] >> 16) + (off >> 24)] = v[k][3];
         }
     }
-    __device__ __forceinline__ void clear(float* __restrict__ d2, int tid) const
+    // zeroes all COUNT * D2_IMS floats of the planes
+    static __device__ __forceinline__ void clear(float* __restrict__ d2, int tid)
     {
+        static_assert(COUNT * D2_IMS % 4 == 0, "16-byte stores");
+        constexpr int T4 = COUNT * D2_IMS / 4;
 #pragma unroll
-        for (int k = 0; k < NV; ++k)
-            if (tid + 256 * k < N) d2[at[k]] = 0.f;
+        for (int i = 0; i < (T4 + 255) / 256; ++i)
+            if (256 * (i + 1) <= T4 || tid + 256 * i < T4)
+                reinterpret_cast<floatx4*>(d2)[tid + 256 * i] = floatx4{0.f, 0.f, 0.f, 0.f};
     }
 };
 
@@ -218,12 +245,27 @@ __global__ __launch_bounds__(256, 2) void conv2_dx_kernel(WorkerBuffers wb, int 
     const int B = wb.B, s_begin = chunk * DX_IPB, s_end = min(B, s_begin + DX_IPB);
     const float* __restrict__ W2 = worker_theta(wb, w) + OFF_W2;
 
-    // B operand of k-step s (flipped tap t' = s/8, output channels 4*(s%8) .. +3): lane (q, l16) holds
-    // W2[4*(s%8)+q][c = l16][8 - t']  (channel groups innermost measured faster here, taps innermost in
-    // the forward kernel)
-    float wreg[72];
+    // K = (output channel o, flipped tap t') = 288, four per MFMA step, one per lane quarter q.  A step's four
+    // are chosen so that its LDS reads need no address arithmetic and few bank conflicts: the 32 lanes an LDS
+    // read serves per cycle are two quarters, and two quarters that read the same plane in the same row (taps
+    // next to each other) touch 17 neighbouring addresses, which is conflict-free, whereas two different planes
+    // or two different rows always collide somewhere (16 positions of 14-wide rows in 16-wide planes span up
+    // to 20 banks).  Per output channel o:
+    //   step X_o: taps (0,0) (0,1) | (1,0) (1,1)     both halves conflict-free
+    //   step Y_o: taps (2,0) (2,1) | (0,2) (1,2)     first half conflict-free
+    // and per four channels one step Z with tap (2,2) of channels 4g .. 4g+3.  Every read is then
+    // lane base + o * plane pitch, an immediate offset, from one of three lane bases per tile.
+    // B operand: lane (q, l16) holds W2[o][c = l16][8 - t'] for its quarter's tap t'.
+    const int tx = q == 0 ? 0 : q == 1 ? 1 : q == 2 ? 3 : 4;   // flipped taps of step X
+    const int ty = q == 0 ? 6 : q == 1 ? 7 : q == 2 ? 2 : 5;   // and of step Y
+    float wx[32], wy[32], wz[8];
 #pragma unroll
-    for (int s = 0; s < 72; ++s) wreg[s] = W2[((4 * (s & 7) + q) * C1 + l16) * 9 + 8 - (s >> 3)];
+    for (int o = 0; o < 32; ++o) {
+        wx[o] = W2[(o * C1 + l16) * 9 + 8 - tx];
+        wy[o] = W2[(o * C1 + l16) * 9 + 8 - ty];
+    }
+#pragma unroll
+    for (int g = 0; g < 8; ++g) wz[g] = W2[((4 * g + q) * C1 + l16) * 9];
 
     for (int i = tid; i < DX_G * D2_IMS / 4; i += 256)
         reinterpret_cast<float4*>(tile)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -262,8 +304,12 @@ __global__ __launch_bounds__(256, 2) void conv2_dx_kernel(WorkerBuffers wb, int 
 #pragma unroll
     for (int i = 0; i < 9; ++i) g1[i] = 0.f;
 
-    const float* a_lane = tile + q * CHS;
+    // lane parts of the three A-operand bases: tap offset (row * 16 + column) of the lane's quarter
+    const float* ax_lane = tile + (tx / 3) * 16 + tx % 3;
+    const float* ay_lane = tile + (ty / 3) * 16 + ty % 3;
+    const float* az_lane = tile + q * CHS + 2 * 16 + 2;
     D2Stage<DX_G, CHS> stage;
+    stage.init(tid);
     stage.prefetch(wb, (size_t)w * B + s_begin, min(DX_G, s_end - s_begin), tid);
     prefetch_x((size_t)w * B + s_begin, min(DX_G, s_end - s_begin));
     int rot = 0;
@@ -277,41 +323,65 @@ __global__ __launch_bounds__(256, 2) void conv2_dx_kernel(WorkerBuffers wb, int 
             stage.prefetch(wb, g0 + DX_G, min(DX_G, s_end - s0 - DX_G), tid);
             prefetch_x(g0 + DX_G, min(DX_G, s_end - s0 - DX_G));
         }
-        for (int t = (wave + rot) & 3; t < (DX_G * P1_POS + 15) / 16; t += 4) {
-            // lane (q, l16) will hold channel l16 at positions 16t + 4q .. +3 (never straddling an image);
-            // fetch their pool1 window bytes (winner, gate) before the matrix work
-            static_assert(DX_G == 2, "image of a position is found with one comparison");
+        // Lane (q, l16) of tile t will hold channel l16 at positions 16t + 4q .. +3 (never straddling an image).
+        // Their pool1 window bytes (winner, gate) are fetched one tile ahead; a position beyond the images of
+        // the group gets zero bytes, whose gate is shut, so the tile needs no branch.
+        static_assert(DX_G == 2, "image of a position is found with one comparison");
+        constexpr int N_TILES = (DX_G * P1_POS + 15) / 16;
+        auto window_bytes = [&](int t) -> uint32_t {
             const int mo = 16 * t + 4 * q, img_o = mo >= P1_POS ? 1 : 0, pos_o = mo - img_o * P1_POS;
-            const bool live = mo < valid * P1_POS;
-            uint32_t win = 0;
-            if (live) win = *reinterpret_cast<const uint32_t*>(wb.am1 + (g0 + img_o) * P1_SIZE + l16 * P1_POS + pos_o);
+            return (t < N_TILES && mo < valid * P1_POS)
+                       ? *reinterpret_cast<const uint32_t*>(wb.am1 + (g0 + img_o) * P1_SIZE + l16 * P1_POS + pos_o)
+                       : 0u;
+        };
+        const int t_first = (wave + rot) & 3;
+        uint32_t win_next = window_bytes(t_first);
+        for (int t = t_first; t < N_TILES; t += 4) {
+            const uint32_t win = win_next;
+            // the 3x3 input neighbourhoods at the four winners: read now, used after the matrix work
+            const int mo = min(16 * t + 4 * q, DX_G * P1_POS - 4), img_o = mo >= P1_POS ? 1 : 0, pos_o = mo - img_o * P1_POS;
+            const float* ximg = xs + img_o * 900;
+            const int4 xo = *reinterpret_cast<const int4*>(x_off + pos_o);  // pos_o is a multiple of 4
+            const int xoff[4] = {xo.x, xo.y, xo.z, xo.w};
+            float xr[4][9];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t bb = win >> (8 * i);
+                const float* px = ximg + xoff[i] + ((bb >> 1) & 1) * 30 + (bb & 1);
+#pragma unroll
+                for (int dy = 0; dy < 3; ++dy)
+#pragma unroll
+                    for (int dx = 0; dx < 3; ++dx) xr[i][dy * 3 + dx] = px[dy * 30 + dx];
+            }
+            win_next = window_bytes(t + 4);
             // A operand: lane row l16 = position 16t + l16 of the group (reads of a row beyond the group
             // are redirected to position 0 and their results dropped)
             const int m = 16 * t + l16;
-            const float* a = a_lane + a_off[m < DX_G * P1_POS ? m : 0];
+            const int at = a_off[m < DX_G * P1_POS ? m : 0];
+            const float* ax = ax_lane + at;
+            const float* ay = ay_lane + at;
+            const float* az = az_lane + at;
             floatx4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int s = 0; s < 72; ++s)
-                acc = mfma16(a[4 * (s & 7) * CHS + ((s >> 3) / 3) * 16 + (s >> 3) % 3], wreg[s], acc);
-            if (live) {
-                const float* ximg = xs + img_o * 900;
-                const int4 xo = *reinterpret_cast<const int4*>(x_off + pos_o);  // pos_o is a multiple of 4
-                const int xoff[4] = {xo.x, xo.y, xo.z, xo.w};
+            for (int g = 0; g < 8; ++g) {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const uint32_t b = win >> (8 * i);
-                    const float v = (b & 4u) ? acc[i] : 0.f;
-                    const float* px = ximg + xoff[i] + ((b >> 1) & 1) * 30 + (b & 1);
-                    gb1 += v;
-#pragma unroll
-                    for (int dy = 0; dy < 3; ++dy)
-#pragma unroll
-                        for (int dx = 0; dx < 3; ++dx) g1[dy * 3 + dx] = fmaf(v, px[dy * 30 + dx], g1[dy * 3 + dx]);
+                for (int j = 0; j < 4; ++j) {
+                    acc = mfma16(ax[(4 * g + j) * CHS], wx[4 * g + j], acc);
+                    acc = mfma16(ay[(4 * g + j) * CHS], wy[4 * g + j], acc);
                 }
+                acc = mfma16(az[4 * g * CHS], wz[g], acc);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float v = ((win >> (8 * i)) & 4u) ? acc[i] : 0.f;
+                gb1 += v;
+#pragma unroll
+                for (int k = 0; k < 9; ++k) g1[k] = fmaf(v, xr[i][k], g1[k]);
             }
         }
         __syncthreads();
-        stage.clear(tile, tid);  // the same thread rewrites these windows at the next commit
+        stage.clear(tile, tid);
+        __syncthreads();  // the planes are cleared by all threads, the next commit scatters into them
     }
 
     // fold the four lane quarters; lanes of quarter 0 hold the wavefront's sums for channel l16
@@ -366,6 +436,7 @@ __global__ __launch_bounds__(256, 2) void conv2_dw_kernel(WorkerBuffers wb)
     const float* p1_lane = p1t + l16 * CHS;
 
     D2Stage<1, CHS> sd;
+    sd.init(tid);
     Pool1Stage<1, CHS> sp;
     if (s_begin < s_end) {
         sd.prefetch(wb, (size_t)w * B + s_begin, 1, tid);
@@ -396,6 +467,7 @@ __global__ __launch_bounds__(256, 2) void conv2_dw_kernel(WorkerBuffers wb)
         }
         __syncthreads();
         sd.clear(d2, tid);
+        __syncthreads();  // cleared by all threads before the next commit scatters into the planes
     }
 
     // accumulator i of tile (mt, j): output channel 16*mt + 4q + i, input channel l16, tap j
