@@ -50,9 +50,12 @@ PEAK_VALU_F32_TFLOPS = 157.3
 # fc2 and its backward have 30 kFLOP per image against 4.1 kB moved (fc1 activations in, d3 out, logits,
 # prediction, label): HBM is their floor
 FC2_BYTES_PER_IMAGE = 512 * 4 + 512 * 4 + 10 * 4 + 4 + 4
-# the final reduction only moves bytes: per worker 32 conv2 partial slots of 4640 floats, 32 conv1 slots of
-# 160, 2 fc2 slots of 5643 in; 4800 + 5643 floats out
-REDUCE_BYTES_PER_WORKER = (32 * 4640 + 32 * 160 + 2 * 5643 + 4800 + 5643) * 4
+# the final reduction only moves bytes: per worker 32 conv2 partial slots of 4640 floats, one conv1 slot of 160 per
+# (8 images, wavefront), 2 fc2 slots of 5643 in; 4800 + 5643 floats out
+def reduce_bytes_per_worker(batch):
+    return (32 * 4640 + 4 * ((batch + 7) // 8) * 160 + 2 * 5643 + 4800 + 5643) * 4
+
+
 # HBM bytes per launch of this workload from the rocprofv3 FETCH_SIZE / WRITE_SIZE passes summarised in
 # profiles/bench_outage_w256_b256_hbm_counters.txt (each scaled by what the same counter reads for the
 # plain 1 GiB copy: x2.000 and x1.000), taken with the kernels as they are in this tree.  A kernel
@@ -114,7 +117,7 @@ def kernel_table(prof, n_workers, batch, drain_rows):
             kernels.append({"kernel": name, "launches": n, "avg_ms": avg, "bound": "hbm", "achieved": ach,
                             "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBPS, "total_ms": ms})
         elif name in ("grad_reduce_kernel", "fc2_kernel"):
-            algo = REDUCE_BYTES_PER_WORKER * n_workers if name == "grad_reduce_kernel" else FC2_BYTES_PER_IMAGE * n_images
+            algo = reduce_bytes_per_worker(batch) * n_workers if name == "grad_reduce_kernel" else FC2_BYTES_PER_IMAGE * n_images
             ach = algo / (avg * 1e-3) / 1e9
             kernels.append({"kernel": name, "launches": n, "avg_ms": avg, "bound": "hbm", "achieved": ach,
                             "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBPS, "total_ms": ms})

@@ -148,7 +148,7 @@ struct D2Stage {
 // worker and walks them FWD_G at a time (196 pooled positions = 49 row tiles per group).
 constexpr int FWD_G = 4, FWD_IPB = 32;
 
-__global__ __launch_bounds__(256, 2) void conv2_fwd_kernel(WorkerBuffers wb, int blocks_per_worker)
+__global__ __launch_bounds__(256, 2) void conv2_fwd_kernel(WorkerBuffers wb, int blocks_per_worker, int ipb)
 {
     constexpr int CHS = CHS_FWD, P1_IMS = C1 * CHS;
     __shared__ __attribute__((aligned(16))) float tile[FWD_G * P1_IMS];  // 67,584 B
@@ -159,7 +159,7 @@ __global__ __launch_bounds__(256, 2) void conv2_fwd_kernel(WorkerBuffers wb, int
     __shared__ uint16_t stage_tab[Pool1Stage<FWD_G, CHS_FWD>::N4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, q = lane >> 4, l16 = lane & 15;
     const int w = blockIdx.x / blocks_per_worker, chunk = blockIdx.x % blocks_per_worker;
-    const int B = wb.B, s_begin = chunk * FWD_IPB, s_end = min(B, s_begin + FWD_IPB);
+    const int B = wb.B, s_begin = chunk * ipb, s_end = min(B, s_begin + ipb);
     const float* __restrict__ W2 = worker_theta(wb, w) + OFF_W2;
     if (tid < FWD_G * P2_POS) {
         const int img = tid / P2_POS, pos = tid % P2_POS;
@@ -230,8 +230,12 @@ __global__ __launch_bounds__(256, 2) void conv2_fwd_kernel(WorkerBuffers wb, int
 // on the vector ALU, which is idle while the matrix cores run.  A block owns up to DX_IPB images of
 // one worker and walks them DX_G at a time; each wavefront's conv1 sums go to its own partial slot.
 constexpr int DX_G = 2, DX_IPB = 32;
+// The conv1 sums leave the registers every DX_FLUSH images, one partial slot per (DX_FLUSH images, wavefront),
+// whatever number of images a block owns (a multiple of DX_FLUSH): the order in which a worker's partial sums
+// are formed and added up then never depends on how the launch was cut into blocks.
+constexpr int DX_FLUSH = 8;
 
-__global__ __launch_bounds__(256, 2) void conv2_dx_kernel(WorkerBuffers wb, int blocks_per_worker)
+__global__ __launch_bounds__(256, 2) void conv2_dx_kernel(WorkerBuffers wb, int blocks_per_worker, int ipb)
 {
     constexpr int CHS = CHS_DX, D2_IMS = C2 * CHS;
     __shared__ __attribute__((aligned(16))) float tile[DX_G * D2_IMS];  // 69,632 B
@@ -242,7 +246,7 @@ __global__ __launch_bounds__(256, 2) void conv2_dx_kernel(WorkerBuffers wb, int 
     __shared__ __attribute__((aligned(16))) int x_off[P1_POS];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, q = lane >> 4, l16 = lane & 15;
     const int w = blockIdx.x / blocks_per_worker, chunk = blockIdx.x % blocks_per_worker;
-    const int B = wb.B, s_begin = chunk * DX_IPB, s_end = min(B, s_begin + DX_IPB);
+    const int B = wb.B, s_begin = chunk * ipb, s_end = min(B, s_begin + ipb);
     const float* __restrict__ W2 = worker_theta(wb, w) + OFF_W2;
 
     // K = (output channel o, flipped tap t') = 288, four per MFMA step, one per lane quarter q.  A step's four
@@ -312,10 +316,10 @@ __global__ __launch_bounds__(256, 2) void conv2_dx_kernel(WorkerBuffers wb, int 
     stage.init(tid);
     stage.prefetch(wb, (size_t)w * B + s_begin, min(DX_G, s_end - s_begin), tid);
     prefetch_x((size_t)w * B + s_begin, min(DX_G, s_end - s_begin));
-    int rot = 0;
-    for (int s0 = s_begin; s0 < s_end; s0 += DX_G, ++rot) {
+    for (int s0 = s_begin; s0 < s_end; s0 += DX_G) {
         const size_t g0 = (size_t)w * B + s0;
         const int valid = min(DX_G, s_end - s0);
+        const int rot = s0 / DX_G;  // which wavefront takes the odd tile depends on the images, not on the block
         stage.commit(tile, tid);
         commit_x();
         __syncthreads();
@@ -381,22 +385,26 @@ __global__ __launch_bounds__(256, 2) void conv2_dx_kernel(WorkerBuffers wb, int 
         }
         __syncthreads();
         stage.clear(tile, tid);
+        if ((s0 + DX_G) % DX_FLUSH == 0 || s0 + DX_G >= s_end) {
+            // fold the four lane quarters; lanes of quarter 0 hold the wavefront's sums for channel l16
+#pragma unroll
+            for (int i = 0; i < 9; ++i) {
+                g1[i] += __shfl_xor(g1[i], 16, 64);
+                g1[i] += __shfl_xor(g1[i], 32, 64);
+            }
+            gb1 += __shfl_xor(gb1, 16, 64);
+            gb1 += __shfl_xor(gb1, 32, 64);
+            if (q == 0) {
+                float* part = wb.part1 + ((size_t)w * (4 * ((B + DX_FLUSH - 1) / DX_FLUSH)) + (s0 / DX_FLUSH) * 4 + wave) * OFF_W2;
+#pragma unroll
+                for (int i = 0; i < 9; ++i) part[OFF_W1 + l16 * 9 + i] = g1[i];
+                part[OFF_B1 + l16] = gb1;
+            }
+#pragma unroll
+            for (int i = 0; i < 9; ++i) g1[i] = 0.f;
+            gb1 = 0.f;
+        }
         __syncthreads();  // the planes are cleared by all threads, the next commit scatters into them
-    }
-
-    // fold the four lane quarters; lanes of quarter 0 hold the wavefront's sums for channel l16
-#pragma unroll
-    for (int i = 0; i < 9; ++i) {
-        g1[i] += __shfl_xor(g1[i], 16, 64);
-        g1[i] += __shfl_xor(g1[i], 32, 64);
-    }
-    gb1 += __shfl_xor(gb1, 16, 64);
-    gb1 += __shfl_xor(gb1, 32, 64);
-    if (q == 0) {
-        float* part = wb.part1 + ((size_t)w * blocks_per_worker * 4 + chunk * 4 + wave) * OFF_W2;
-#pragma unroll
-        for (int i = 0; i < 9; ++i) part[OFF_W1 + l16 * 9 + i] = g1[i];
-        part[OFF_B1 + l16] = gb1;
     }
 }
 
@@ -490,18 +498,34 @@ __global__ __launch_bounds__(256, 2) void conv2_dw_kernel(WorkerBuffers wb)
 
 }  // namespace
 
-void launch_conv2_fwd(const WorkerBuffers& wb, hipStream_t s)
+// Images per block: as many as FWD_IPB / DX_IPB when the launch still fills every compute unit twice over
+// (two blocks fit a unit), else fewer (16, 8), so that a small launch does not leave half the chip idle.
+static int images_per_block(int n, int batch, int most)
 {
-    const int bpw = (wb.B + FWD_IPB - 1) / FWD_IPB;
-    hipLaunchKernelGGL(conv2_fwd_kernel, dim3(wb.n * bpw), dim3(256), 0, s, wb, bpw);
+    static int slots = 0;
+    if (slots == 0) {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+            cus = 256;
+        slots = 2 * cus;
+    }
+    int ipb = most;
+    while (ipb > DX_FLUSH && n * ((batch + ipb - 1) / ipb) < slots) ipb /= 2;
+    return ipb;
 }
 
-int conv1_part_slots(int batch) { return 4 * ((batch + DX_IPB - 1) / DX_IPB); }
+void launch_conv2_fwd(const WorkerBuffers& wb, hipStream_t s)
+{
+    const int ipb = images_per_block(wb.n, wb.B, FWD_IPB), bpw = (wb.B + ipb - 1) / ipb;
+    hipLaunchKernelGGL(conv2_fwd_kernel, dim3(wb.n * bpw), dim3(256), 0, s, wb, bpw, ipb);
+}
+
+int conv1_part_slots(int batch) { return 4 * ((batch + DX_FLUSH - 1) / DX_FLUSH); }
 
 void launch_conv2_dx(const WorkerBuffers& wb, hipStream_t s)
 {
-    const int bpw = (wb.B + DX_IPB - 1) / DX_IPB;
-    hipLaunchKernelGGL(conv2_dx_kernel, dim3(wb.n * bpw), dim3(256), 0, s, wb, bpw);
+    const int ipb = images_per_block(wb.n, wb.B, DX_IPB), bpw = (wb.B + ipb - 1) / ipb;
+    hipLaunchKernelGGL(conv2_dx_kernel, dim3(wb.n * bpw), dim3(256), 0, s, wb, bpw, ipb);
 }
 
 void launch_conv2_dw(const WorkerBuffers& wb, hipStream_t s)

@@ -84,9 +84,21 @@ struct Fc1DwEpi {
 constexpr int FEAT_WIDE = P2_SIZE / 128 * 128;  // 1536
 
 // forward: rows = 512 units (W3, k-contiguous), columns = the worker's samples (pool2, k-contiguous)
+// A launch too small to give every compute unit two 128 x 128 tiles is cut into 64 x 128 tiles instead (the
+// order in which a value's products are added up does not depend on the tile shape).
 void launch_fc1_fwd(const WorkerBuffers& wb, hipStream_t s)
 {
-    gemm_launch<GemmCfg<true, true, 2, 2, 2, 2, 16>, 1>(FC1, wb.B, P2_SIZE, P2_SIZE, P2_SIZE, wb.n, Fc1FwdEpi{wb}, s);
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+            cus = 256;
+    }
+    const int wide_tiles = (FC1 / 128) * ((wb.B + 127) / 128) * wb.n;
+    if (wide_tiles >= 2 * cus)
+        gemm_launch<GemmCfg<true, true, 2, 2, 2, 2, 16>, 1>(FC1, wb.B, P2_SIZE, P2_SIZE, P2_SIZE, wb.n, Fc1FwdEpi{wb}, s);
+    else
+        gemm_launch<GemmCfg<true, true, 1, 2, 2, 2, 16>, 1>(FC1, wb.B, P2_SIZE, P2_SIZE, P2_SIZE, wb.n, Fc1FwdEpi{wb}, s);
 }
 
 // weight gradient: rows = 512 units (d3, row-contiguous), columns = 1568 features (pool2, row-contiguous),

@@ -12,23 +12,41 @@ namespace ps {
 namespace {
 
 // Sums the partial slots in fixed order into the worker's queue entry: conv1 tensors have one partial
-// per wavefront of conv2's input-gradient kernel, conv2 tensors one per (chunk, wavefront) of its
+// per (8 images, wavefront) of conv2's input-gradient kernel, conv2 tensors one per (chunk, wavefront) of its
 // weight-gradient kernel, fc2 tensors, fc1 bias and the loss one per block of the fc2 kernel.
+// Grid (workers, REDUCE_Y) x 256 threads.  The 160 conv1 values have many slots each (128 at 256 images), so
+// a block takes 20 of them with 12 threads per value (thread j adds slots j, j + 12, ... in order, thread 0
+// then adds the 12 sums in order); everything else is one thread per value over the few slots it has.
+constexpr int REDUCE_Y = 8, C1_PER_BLOCK = OFF_W2 / REDUCE_Y, C1_LANES = 12;
+static_assert(C1_PER_BLOCK * REDUCE_Y == OFF_W2 && C1_PER_BLOCK * C1_LANES <= 256, "conv1 values over the blocks");
+
 __global__ __launch_bounds__(256) void grad_reduce_kernel(WorkerBuffers wb, int fc2_slots, int c1_slots)
 {
+    __shared__ float c1_sum[C1_PER_BLOCK][C1_LANES + 1];
     const int w = blockIdx.x;
     float* grad = worker_grad(wb, w);
-    const float* part = wb.part + (size_t)w * N_PART * CONV_PART;
-    const int tid = blockIdx.y * 256 + threadIdx.x, stride = gridDim.y * 256;
-    for (int i = tid; i < CONV_PART; i += stride) {
-        float sum = 0.f;
-        if (i < OFF_W2) {
-            const float* p1 = wb.part1 + (size_t)w * c1_slots * OFF_W2 + i;
-            for (int c = 0; c < c1_slots; ++c) sum += p1[(size_t)c * OFF_W2];
-        } else {
-#pragma unroll
-            for (int c = 0; c < N_PART; ++c) sum += part[(size_t)c * CONV_PART + i];
+    {
+        const int e = threadIdx.x / C1_LANES, j = threadIdx.x % C1_LANES;
+        if (e < C1_PER_BLOCK) {
+            const float* p1 = wb.part1 + (size_t)w * c1_slots * OFF_W2 + blockIdx.y * C1_PER_BLOCK + e;
+            float sum = 0.f;
+            for (int c = j; c < c1_slots; c += C1_LANES) sum += p1[(size_t)c * OFF_W2];
+            c1_sum[e][j] = sum;
         }
+        __syncthreads();
+        if (threadIdx.x < C1_PER_BLOCK) {
+            float sum = 0.f;
+#pragma unroll
+            for (int j2 = 0; j2 < C1_LANES; ++j2) sum += c1_sum[threadIdx.x][j2];
+            grad[blockIdx.y * C1_PER_BLOCK + threadIdx.x] = sum;
+        }
+    }
+    const float* part = wb.part + (size_t)w * N_PART * CONV_PART;
+    const int tid = blockIdx.y * 256 + threadIdx.x, stride = REDUCE_Y * 256;
+    for (int i = OFF_W2 + tid; i < CONV_PART; i += stride) {
+        float sum = 0.f;
+#pragma unroll
+        for (int c = 0; c < N_PART; ++c) sum += part[(size_t)c * CONV_PART + i];
         grad[i] = sum;
     }
     const float* fpart = wb.fpart + (size_t)w * fc2_slots * FC2_PART;
@@ -86,7 +104,7 @@ hipError_t launch_worker_backward(const WorkerBuffers& wb, hipStream_t s, Profil
     PS_TIMED(K_FC1_DX, launch_fc1_dx(wb, s));
     PS_TIMED(K_CONV2_DW, launch_conv2_dw(wb, s));
     PS_TIMED(K_CONV2_DX, launch_conv2_dx(wb, s));
-    PS_TIMED(K_GRAD_REDUCE, hipLaunchKernelGGL(grad_reduce_kernel, dim3(wb.n, 8), dim3(256), 0, s, wb, fc2_split(wb.n),
+    PS_TIMED(K_GRAD_REDUCE, hipLaunchKernelGGL(grad_reduce_kernel, dim3(wb.n, REDUCE_Y), dim3(256), 0, s, wb, fc2_split(wb.n),
                                                 conv1_part_slots(wb.B)));
     return hipGetLastError();
 }
