@@ -35,15 +35,26 @@ struct Pool1Stage {
     static constexpr int P1_IMS = C1 * CHS;
     static constexpr int N4 = COUNT * (P1_SIZE / 4), NV = (N4 + 255) / 256;
     floatx4 v[NV];
+    uint32_t src[NV];  // float offset of this thread's k-th float4 inside a group of COUNT images
+    __device__ __forceinline__ void init(int tid)
+    {
+#pragma unroll
+        for (int k = 0; k < NV; ++k) src[k] = (uint32_t)min(tid + 256 * k, N4 - 1) * 4;  // threads without an element repeat the last one
+    }
     // images [g0, g0 + valid) exist; the rest of the group repeats the last existing image (its
     // results are never stored), so the loads need no branches
     __device__ __forceinline__ void prefetch(const float* __restrict__ p1, size_t g0, int valid, int tid)
     {
+        const float* group = p1 + g0 * P1_SIZE;
+        if (valid >= COUNT) {  // uniform over the block
 #pragma unroll
-        for (int k = 0; k < NV; ++k) {
-            const int i4 = min(tid + 256 * k, N4 - 1);
-            const int img = min(i4 / (P1_SIZE / 4), valid - 1);
-            v[k] = *reinterpret_cast<const floatx4*>(p1 + (g0 + img) * P1_SIZE + (size_t)(i4 % (P1_SIZE / 4)) * 4);
+            for (int k = 0; k < NV; ++k) v[k] = *reinterpret_cast<const floatx4*>(group + src[k]);
+        } else {
+#pragma unroll
+            for (int k = 0; k < NV; ++k) {
+                const uint32_t img = min(src[k] / P1_SIZE, (uint32_t)(valid - 1));
+                v[k] = *reinterpret_cast<const floatx4*>(group + img * P1_SIZE + src[k] % P1_SIZE);
+            }
         }
     }
     // Where the float4s land does not change from group to group: a table (bits 0-14 the offset of
@@ -184,6 +195,7 @@ __global__ __launch_bounds__(256, 2) void conv2_fwd_kernel(WorkerBuffers wb, int
     // this lane's part of the A operand address: channel quarter, window element
     const float* a_lane = tile + q * CHS + ((l16 >> 1) & 1) * 16 + (l16 & 1);
     Pool1Stage<FWD_G, CHS> stage;
+    stage.init(tid);
     stage.prefetch(wb.p1, (size_t)w * B + s_begin, min(FWD_G, s_end - s_begin), tid);
     int rot = 0;
     for (int s0 = s_begin; s0 < s_end; s0 += FWD_G, ++rot) {
@@ -206,11 +218,12 @@ __global__ __launch_bounds__(256, 2) void conv2_fwd_kernel(WorkerBuffers wb, int
             const int ppo = 4 * t + q;
             if (ppo < valid * P2_POS) {
                 const size_t out = g0 * P2_SIZE + out_off[ppo];
+                // the four values of a window share their channel's bias: it is added to the winner only
                 int code;
-                float best = pool_first_max(acc0[0] + bias0, acc0[1] + bias0, acc0[2] + bias0, acc0[3] + bias0, code);
+                float best = pool_first_max(acc0[0], acc0[1], acc0[2], acc0[3], code) + bias0;
                 wb.p2[out + l16 * P2_POS] = fmaxf(best, 0.f);
                 wb.am2[out + l16 * P2_POS] = (uint8_t)(code | (best > 0.f ? 4 : 0));
-                best = pool_first_max(acc1[0] + bias1, acc1[1] + bias1, acc1[2] + bias1, acc1[3] + bias1, code);
+                best = pool_first_max(acc1[0], acc1[1], acc1[2], acc1[3], code) + bias1;
                 wb.p2[out + (l16 + 16) * P2_POS] = fmaxf(best, 0.f);
                 wb.am2[out + (l16 + 16) * P2_POS] = (uint8_t)(code | (best > 0.f ? 4 : 0));
             }
@@ -446,6 +459,7 @@ __global__ __launch_bounds__(256, 2) void conv2_dw_kernel(WorkerBuffers wb)
     D2Stage<1, CHS> sd;
     sd.init(tid);
     Pool1Stage<1, CHS> sp;
+    sp.init(tid);
     if (s_begin < s_end) {
         sd.prefetch(wb, (size_t)w * B + s_begin, 1, tid);
         sp.prefetch(wb.p1, (size_t)w * B + s_begin, 1, tid);
