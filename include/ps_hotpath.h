@@ -353,6 +353,9 @@ PS_API const char* ps_profile_kernel_name(int32_t kernel_id);
  *   shared_simd_ms[0..2]                        the same MFMA loop alone, a vector-FMA loop alone, and both as
  *                                               two wavefronts sharing every SIMD: [2] near max([0], [1]) means
  *                                               the two kinds overlap, near [0] + [1] that they do not
+ *   ns_per_mfma_with_lds_reads[i]               SIMD time per 16x16x4 MFMA when i = 0, 1, 2 values per MFMA and lane
+ *                                               come out of LDS (ds_read_b32, no bank conflicts; two blocks of four
+ *                                               wavefronts per compute unit)
  *   hbm_read_GBps / hbm_copy_GBps               one pass of 16-byte loads over the buffer / copy of one half to
  *                                               the other (bytes read + bytes written) */
 typedef struct {
@@ -361,6 +364,7 @@ typedef struct {
     double ns_per_mfma_16x16x4;
     double ns_per_mfma_with_valu[4];
     double shared_simd_ms[3];
+    double ns_per_mfma_with_lds_reads[3];
     double hbm_read_GBps, hbm_copy_GBps;
     uint64_t hbm_read_bytes;
 } ps_ceilings;

@@ -57,7 +57,7 @@ class ps_ceilings(ctypes.Structure):
     _fields_ = [("compute_units", ctypes.c_int32), ("mfma_32x32x2_tflops", ctypes.c_double),
                 ("mfma_32x32x2_first_launch_tflops", ctypes.c_double), ("mfma_16x16x4_tflops", ctypes.c_double),
                 ("ns_per_mfma_16x16x4", ctypes.c_double), ("ns_per_mfma_with_valu", ctypes.c_double * 4),
-                ("shared_simd_ms", ctypes.c_double * 3), ("hbm_read_GBps", ctypes.c_double), ("hbm_copy_GBps", ctypes.c_double),
+                ("shared_simd_ms", ctypes.c_double * 3), ("ns_per_mfma_with_lds_reads", ctypes.c_double * 3), ("hbm_read_GBps", ctypes.c_double), ("hbm_copy_GBps", ctypes.c_double),
                 ("hbm_read_bytes", ctypes.c_uint64)]
 
 

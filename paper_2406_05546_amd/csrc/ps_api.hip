@@ -958,6 +958,14 @@ ps_status ps_debug_last_batch(ps_ctx* c, int32_t i, uint8_t* pool1_host, uint8_t
         PS_HIP(c, hipMemcpyAsync(keep_host, c->at<uint8_t>(c->lay.keep), B * FC1, hipMemcpyDeviceToHost, s));
     }
     PS_HIP(c, hipStreamSynchronize(s));
+    if (pool1_host) {
+        // pool1 window bytes are kept as (winner's offset in a 30-wide image, gate in bit 7); the caller gets
+        // the documented form: bits 0-1 winner dy*2+dx, bit 2 gate
+        for (size_t i = 0; i < B * P1_SIZE; ++i) {
+            const uint8_t b = pool1_host[i], off = b & 0x7f;
+            pool1_host[i] = (uint8_t)((off & 1) | (off >= 30 ? 2 : 0) | ((b & AM1_GATE) ? 4 : 0));
+        }
+    }
     return PS_OK;
 }
 

@@ -73,6 +73,30 @@ __global__ __launch_bounds__(512) void shared_simd_kernel(float* out, int iters,
     if (kind == 2) mixed_loop<4, 0>(out, iters, a, b);
 }
 
+// 16x16x4 MFMAs whose A operand comes out of LDS: READS values read per MFMA (0: operands from registers;
+// 1: one ds_read_b32 per MFMA, consecutive lanes on consecutive banks; 2: a second value read and added up on
+// the side).  Two blocks per compute unit, as the conv2 kernels run.
+template <int READS>
+__global__ __launch_bounds__(256, 2) void mfma16_lds_kernel(float* out, int iters, float b)
+{
+    __shared__ __attribute__((aligned(16))) float lds[16384];
+    for (int i = threadIdx.x; i < 16384; i += 256) lds[i] = (float)(i & 7);
+    __syncthreads();
+    const float* p = lds + (threadIdx.x & 63) + (threadIdx.x >> 6) * 2048;
+    floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+    float side = 0.f;
+    for (int i = 0; i < iters; ++i) {
+        const float* q = p + (i & 3) * 256;  // stays inside the wavefront's 2048 + 1024 + 16 * 272 floats < 16384
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            if (READS >= 2) side += q[u * 272 + 64];
+            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(READS >= 1 ? q[u * 272] : b, b, acc, 0, 0, 0);
+        }
+    }
+    const float s = acc[0] + acc[1] + acc[2] + acc[3] + side;
+    if (s == 12345.678f) out[threadIdx.x] = s;
+}
+
 __device__ __forceinline__ floatx4 ld_nt(const floatx4* p) { return __builtin_nontemporal_load(p); }
 
 // Reads `rows` rows of row4 float4 once, in the drain kernel's geometry: one-wavefront blocks, a lane owns
@@ -188,6 +212,15 @@ extern "C" ps_status ps_measure_ceilings(void* workspace_dev, uint64_t workspace
     out->shared_simd_ms[0] = t.median([&] { hipLaunchKernelGGL(shared_simd_kernel, dim3(cus), dim3(512), 0, s, sink, iters16, 1.f, 1.f, 1, 0); }, 5);
     out->shared_simd_ms[1] = t.median([&] { hipLaunchKernelGGL(shared_simd_kernel, dim3(cus), dim3(512), 0, s, sink, iters16, 1.f, 1.f, 0, 2); }, 5);
     out->shared_simd_ms[2] = t.median([&] { hipLaunchKernelGGL(shared_simd_kernel, dim3(cus), dim3(512), 0, s, sink, iters16, 1.f, 1.f, 1, 2); }, 5);
+
+    // MFMAs fed from LDS, two blocks of four wavefronts per compute unit
+    {
+        const int itl = 8000;
+        const double per = 1e6 / (itl * 16.0 * 2.0);  // two wavefronts share a SIMD: ns of SIMD time per MFMA
+        out->ns_per_mfma_with_lds_reads[0] = per * t.median([&] { hipLaunchKernelGGL(mfma16_lds_kernel<0>, dim3(2 * cus), dim3(256), 0, s, sink, itl, 1.f); }, 5);
+        out->ns_per_mfma_with_lds_reads[1] = per * t.median([&] { hipLaunchKernelGGL(mfma16_lds_kernel<1>, dim3(2 * cus), dim3(256), 0, s, sink, itl, 1.f); }, 5);
+        out->ns_per_mfma_with_lds_reads[2] = per * t.median([&] { hipLaunchKernelGGL(mfma16_lds_kernel<2>, dim3(2 * cus), dim3(256), 0, s, sink, itl, 1.f); }, 5);
+    }
 
     // HBM streams over the workspace (at most 4 GiB of it): read once; copy first half to second half
     const uint64_t bytes = std::min<uint64_t>(workspace_bytes, 4ull << 30) & ~uint64_t(511);

@@ -24,6 +24,8 @@ constexpr int CONV_PART = OFF_W3;  // conv1 + conv2 gradient floats (4800), redu
 constexpr int N_CHUNK = 8;         // image chunks per worker in the conv weight-gradient reductions
 constexpr int N_PART = 4 * N_CHUNK;  // partial slots per worker: one per (chunk, wavefront) of conv2's kernel
 
+constexpr int AM1_GATE = 0x80;  // pool1 window byte: winner's pre-activation > 0
+
 // One worker of a batched call.
 struct WorkerMeta {
     int32_t slot;    // ring slot of the snapshot it reads
@@ -40,7 +42,8 @@ struct WorkerBuffers {
     const float* x;      // [n*B][784]
     const int32_t* y;    // [n*B]
     float* p1;           // [n*B][16][196]  conv1 -> ReLU -> pool
-    uint8_t* am1;        // [n*B][16][196]  bits 0-1 window winner, bit 2 winner > 0
+    uint8_t* am1;        // [n*B][16][196]  bits 0-6 the window winner's offset dy*30 + dx in a 30-wide padded input
+                         //                 image (0, 1, 30, 31), bit 7 winner > 0: what conv1's weight gradient needs
     float* p2;           // [n*B][32][49]
     uint8_t* am2;        // [n*B][32][49]
     float* ht;           // [n*B][512]      fc1 -> ReLU -> dropout

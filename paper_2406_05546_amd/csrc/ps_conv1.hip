@@ -27,11 +27,15 @@ __device__ __forceinline__ void conv1_pair(const WorkerBuffers& wb, const float*
                 for (int dx = 0; dx < 3; ++dx) acc = fmaf(k[dy * 3 + dx], patch[a + dy][b + dx], acc);
             v[a * 2 + b] = acc;
         }
-    int code;
-    const float best = pool_first_max(v[0], v[1], v[2], v[3], code);
+    // first maximum in scan order; the winner is kept as its offset in a 30-wide padded input image
+    float best = v[0];
+    int off = 0;
+    if (v[1] > best) { best = v[1]; off = 1; }
+    if (v[2] > best) { best = v[2]; off = 30; }
+    if (v[3] > best) { best = v[3]; off = 31; }
     const size_t out = g * P1_SIZE + o * P1_POS + pos;
     wb.p1[out] = fmaxf(best, 0.f);
-    wb.am1[out] = (uint8_t)(code | (best > 0.f ? 4 : 0));
+    wb.am1[out] = (uint8_t)(off | (best > 0.f ? AM1_GATE : 0));
 }
 
 // conv1 (1 -> 16, 3x3, pad 1) + ReLU + 2x2 max pool.  The kernel is bound by vector-ALU issue, and 196

@@ -341,59 +341,76 @@ __global__ __launch_bounds__(256, 2) void conv2_dx_kernel(WorkerBuffers wb, int 
             prefetch_x(g0 + DX_G, min(DX_G, s_end - s0 - DX_G));
         }
         // Lane (q, l16) of tile t will hold channel l16 at positions 16t + 4q .. +3 (never straddling an image).
-        // Their pool1 window bytes (winner, gate) are fetched one tile ahead; a position beyond the images of
-        // the group gets zero bytes, whose gate is shut, so the tile needs no branch.
+        // Their pool1 window bytes (winner's offset in the padded input image, gate) are fetched one tile ahead;
+        // a position beyond the images of the group gets zero bytes, whose gate is shut, so the tile needs no
+        // branch.  The 36 input pixels of conv1's weight gradient are read in front of the matrix work and used
+        // behind it; the first A-operand values of the next tile are read during the current one, so that the
+        // matrix cores do not wait behind those 36 reads at the start of a tile (LDS reads return in order).
         static_assert(DX_G == 2, "image of a position is found with one comparison");
-        constexpr int N_TILES = (DX_G * P1_POS + 15) / 16;
+        constexpr int N_TILES = (DX_G * P1_POS + 15) / 16, AHEAD = 4;  // A values of channels 0 .. AHEAD-1 read ahead
+        const uint8_t* am1_lane = wb.am1 + g0 * P1_SIZE + l16 * P1_POS + 4 * q;
         auto window_bytes = [&](int t) -> uint32_t {
-            const int mo = 16 * t + 4 * q, img_o = mo >= P1_POS ? 1 : 0, pos_o = mo - img_o * P1_POS;
+            const int mo = 16 * t + 4 * q;  // position in the group; the second image starts P1_SIZE bytes after the first
             return (t < N_TILES && mo < valid * P1_POS)
-                       ? *reinterpret_cast<const uint32_t*>(wb.am1 + (g0 + img_o) * P1_SIZE + l16 * P1_POS + pos_o)
+                       ? *reinterpret_cast<const uint32_t*>(am1_lane + 16 * t + (mo >= P1_POS ? P1_SIZE - P1_POS : 0))
                        : 0u;
+        };
+        auto a_base = [&](int t) -> int {
+            const int m = 16 * t + l16;  // lane row l16 = position 16t + l16 of the group (rows beyond it read position 0)
+            return a_off[m < DX_G * P1_POS ? m : 0];
         };
         const int t_first = (wave + rot) & 3;
         uint32_t win_next = window_bytes(t_first);
+        int at = a_base(t_first);
+        float ax_next[AHEAD], ay_next[AHEAD];
+#pragma unroll
+        for (int o = 0; o < AHEAD; ++o) {
+            ax_next[o] = ax_lane[at + o * CHS];
+            ay_next[o] = ay_lane[at + o * CHS];
+        }
         for (int t = t_first; t < N_TILES; t += 4) {
             const uint32_t win = win_next;
-            // the 3x3 input neighbourhoods at the four winners: read now, used after the matrix work
+            // the 3x3 input neighbourhoods at the four winners
             const int mo = min(16 * t + 4 * q, DX_G * P1_POS - 4), img_o = mo >= P1_POS ? 1 : 0, pos_o = mo - img_o * P1_POS;
             const float* ximg = xs + img_o * 900;
             const int4 xo = *reinterpret_cast<const int4*>(x_off + pos_o);  // pos_o is a multiple of 4
-            const int xoff[4] = {xo.x, xo.y, xo.z, xo.w};
-            float xr[4][9];
+            const float* px[4] = {ximg + xo.x + (win & 0x7fu), ximg + xo.y + ((win >> 8) & 0x7fu),
+                                  ximg + xo.z + ((win >> 16) & 0x7fu), ximg + xo.w + ((win >> 24) & 0x7fu)};
+            float xr[36];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const uint32_t bb = win >> (8 * i);
-                const float* px = ximg + xoff[i] + ((bb >> 1) & 1) * 30 + (bb & 1);
-#pragma unroll
-                for (int dy = 0; dy < 3; ++dy)
-#pragma unroll
-                    for (int dx = 0; dx < 3; ++dx) xr[i][dy * 3 + dx] = px[dy * 30 + dx];
-            }
+            for (int r = 0; r < 36; ++r) xr[r] = px[r / 9][((r % 9) / 3) * 30 + (r % 9) % 3];
             win_next = window_bytes(t + 4);
-            // A operand: lane row l16 = position 16t + l16 of the group (reads of a row beyond the group
-            // are redirected to position 0 and their results dropped)
-            const int m = 16 * t + l16;
-            const int at = a_off[m < DX_G * P1_POS ? m : 0];
             const float* ax = ax_lane + at;
             const float* ay = ay_lane + at;
             const float* az = az_lane + at;
+            const int at_next = a_base(min(t + 4, N_TILES - 1));
             floatx4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int g = 0; g < 8; ++g) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    acc = mfma16(ax[(4 * g + j) * CHS], wx[4 * g + j], acc);
-                    acc = mfma16(ay[(4 * g + j) * CHS], wy[4 * g + j], acc);
+                    const int o = 4 * g + j;
+                    acc = mfma16(o < AHEAD ? ax_next[o] : ax[o * CHS], wx[o], acc);
+                    acc = mfma16(o < AHEAD ? ay_next[o] : ay[o * CHS], wy[o], acc);
                 }
                 acc = mfma16(az[4 * g * CHS], wz[g], acc);
+                if (g == 6) {  // the next tile's first reads: their operands above are consumed by now
+#pragma unroll
+                    for (int o = 0; o < AHEAD; ++o) {
+                        ax_next[o] = ax_lane[at_next + o * CHS];
+                        ay_next[o] = ay_lane[at_next + o * CHS];
+                    }
+                }
             }
+            at = at_next;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const float v = ((win >> (8 * i)) & 4u) ? acc[i] : 0.f;
+                // gate bit -> all ones or zero
+                const uint32_t keep = (uint32_t)((int32_t)(win << (24 - 8 * i)) >> 31);
+                const float v = __uint_as_float(__float_as_uint(acc[i]) & keep);
                 gb1 += v;
 #pragma unroll
-                for (int k = 0; k < 9; ++k) g1[k] = fmaf(v, xr[i][k], g1[k]);
+                for (int k = 0; k < 9; ++k) g1[k] = fmaf(v, xr[9 * i + k], g1[k]);
             }
         }
         __syncthreads();
