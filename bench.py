@@ -56,23 +56,47 @@ def reduce_bytes_per_worker(batch):
     return (32 * 4640 + 4 * ((batch + 7) // 8) * 160 + 2 * 5643 + 4800 + 5643) * 4
 
 
-# HBM bytes per launch of this workload from the rocprofv3 FETCH_SIZE / WRITE_SIZE passes summarised in
-# profiles/bench_outage_w256_b256_hbm_counters.txt (each scaled by what the same counter reads for the
-# plain 1 GiB copy: x2.000 and x1.000), taken with the kernels as they are in this tree.  A kernel
-# that changes afterwards must be set to None here until its counters are taken again.
+# HBM bytes per launch of the main workload come from the tracked rocprofv3 counter summary (FETCH_SIZE and
+# WRITE_SIZE passes, each scaled by what the same counter reads for a plain copy of known size), not from
+# this run: bench.py reads the summary file, so the figures cannot drift from it.  A kernel that has
+# changed since the counters were taken must be listed in STALE_COUNTERS until they are taken again.
 MIB = 1 << 20
-MEASURED_HBM_BYTES = {
-    "conv1_fwd_kernel": (196.9 + 1014.1) * MIB, "conv2_fwd_kernel": (785.1 + 494.6) * MIB,
-    "gemm_f32_mfma<Fc1FwdEpi>": (578.3 + 130.8) * MIB, "fc2_kernel": (128.6 + 141.8) * MIB,
-    # weight / input gradient: one launch each, wide tiles plus narrow tiles for the feature edge
-    "gemm_f32_mfma<Fc1DwEpi>": (659.6 + 784.0) * MIB,
-    "gemm_f32_mfma<Fc1DxEpi>": (941.2 + 392.3) * MIB,
-    "conv2_dw_kernel": (1274.2 + 145.0) * MIB, "conv2_dx_kernel": (883.2 + 20.0) * MIB,
-    "grad_reduce_kernel": (176.2 + 10.2) * MIB, "apply_kernel<0>": (3180.1 + 3.1) * MIB,
-    "apply_kernel<1>": (3180.2 + 3.1) * MIB, "grad_sqnorm_kernel": (3214.8 + 1.0) * MIB,
-    "apply_kernel<1, clip>": (3180.2 + 3.1) * MIB, "apply_adadelta_kernel": (3186.4 + 9.3) * MIB,
-    "elastic_average_kernel": (797.4 + 797.3) * MIB,
-}
+COUNTER_SUMMARY = os.path.join(ROOT, "profiles", "bench_outage_w256_b256_hbm_counters.txt")
+COUNTER_ROWS = {"conv1_fwd_kernel": "conv1_fwd_kernel", "conv2_fwd_kernel": "conv2_fwd_kernel", "fc2_kernel": "::fc2_kernel",
+                "gemm_f32_mfma<Fc1FwdEpi>": "gemm_f32_mfma<ps::GemmCfg<true, true",
+                "gemm_f32_mfma<Fc1DwEpi>": "gemm_f32_mfma_edge<ps::GemmCfg<false, false",
+                "gemm_f32_mfma<Fc1DxEpi>": "gemm_f32_mfma_edge<ps::GemmCfg<false, true", "conv2_dw_kernel": "conv2_dw_kernel",
+                "conv2_dx_kernel": "conv2_dx_kernel", "grad_reduce_kernel": "grad_reduce_kernel",
+                "grad_sqnorm_kernel": "grad_sqnorm_kernel", "apply_adadelta_kernel": "apply_adadelta_kernel",
+                "elastic_average_kernel": "elastic_average_kernel", "apply_kernel<0>": "apply_kernel<0, false>",
+                "apply_kernel<1>": "apply_kernel<1, false>", "apply_kernel<1, clip>": "apply_kernel<1, true>"}
+STALE_COUNTERS = ()
+
+
+def measured_hbm_bytes(path=COUNTER_SUMMARY):
+    """{kernel: HBM bytes per launch} from the tracked summary; {} if the file is not there.  Worker kernels:
+    mean over dispatches; apply kernels: the largest dispatch, which is the 1024-row drain."""
+    if not os.path.exists(path):
+        return {}
+    rows = {}
+    for line in open(path):
+        parts = line.split()
+        if len(parts) >= 8 and line.startswith(("ps::", "void ps::")):
+            try:
+                _, _, f_mib, _, w_mib, max_f, max_w = (float(v) for v in parts[-7:])
+            except ValueError:
+                continue
+            rows[line[:80]] = (f_mib, w_mib, max_f, max_w)
+    out = {}
+    for name, key in COUNTER_ROWS.items():
+        hit = [v for k, v in rows.items() if key in k]
+        if len(hit) == 1 and name not in STALE_COUNTERS:
+            f_mib, w_mib, max_f, max_w = hit[0]
+            out[name] = ((max_f + max_w) if name.startswith("apply_kernel") else (f_mib + w_mib)) * MIB
+    return out
+
+
+MEASURED_HBM_BYTES = measured_hbm_bytes()
 
 
 def cpu_baseline():
@@ -81,7 +105,7 @@ def cpu_baseline():
     from oracle import oracle as orc
     from paper_2406_05546_amd import synth
     threads = min(16, len(os.sched_getaffinity(0)))
-    n = 4 * threads                                        # four 256-image workers per thread
+    n = 24 * threads                                       # 24 256-image workers per thread: about 10 s of oracle work
     mbs = [synth.minibatch_id(w, 0) for w in range(n)]
     x, y = synth.minibatches(1, mbs, B)
     theta = synth.he_uniform_theta(1).astype(np.float64)
