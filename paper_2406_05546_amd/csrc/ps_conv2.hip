@@ -93,10 +93,10 @@ struct Pool1Stage {
 // the window never changes, so those offsets are computed once per block (two 16-bit offsets per
 // register) and a commit costs a handful of vector instructions per value instead of the divisions by 49
 // and 7.  Before the next commit the planes are cleared as a whole with 16-byte stores.
-template <int COUNT, int CHS>
+template <int COUNT, int CHS, int NT = 256>
 struct D2Stage {
     static constexpr int D2_IMS = C2 * CHS;
-    static constexpr int N4 = COUNT * (P2_SIZE / 4), NV = (N4 + 255) / 256;
+    static constexpr int N4 = COUNT * (P2_SIZE / 4), NV = (N4 + NT - 1) / NT;
     static_assert(P2_SIZE % 4 == 0, "a group of four values never straddles two images");
     static_assert(COUNT * D2_IMS < (1 << 16), "offsets must fit 16 bits");
     floatx4 v[NV];
@@ -109,7 +109,7 @@ struct D2Stage {
             uint32_t b[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const int e = min(4 * (tid + 256 * k), COUNT * P2_SIZE - 4) + j;
+                const int e = min(4 * (tid + NT * k), COUNT * P2_SIZE - 4) + j;
                 const int img = e / P2_SIZE, r = e % P2_SIZE, o = r / P2_POS, p = r % P2_POS;
                 b[j] = (uint32_t)(img * D2_IMS + o * CHS + (2 * (p / P2_W) + 1) * 16 + 2 * (p % P2_W) + 1);
             }
@@ -121,8 +121,8 @@ struct D2Stage {
     {
 #pragma unroll
         for (int k = 0; k < NV; ++k) {
-            const int i4 = tid + 256 * k;
-            const bool ok = (256 * (k + 1) <= N4 || i4 < N4) && (4 * i4) / P2_SIZE < valid;
+            const int i4 = tid + NT * k;
+            const bool ok = (NT * (k + 1) <= N4 || i4 < N4) && (4 * i4) / P2_SIZE < valid;
             v[k] = ok ? *reinterpret_cast<const floatx4*>(wb.dp2g + g0 * P2_SIZE + (size_t)i4 * 4) : floatx4{0.f, 0.f, 0.f, 0.f};
             code[k] = ok ? *reinterpret_cast<const uint32_t*>(wb.am2 + g0 * P2_SIZE + (size_t)i4 * 4) : 0u;
         }
@@ -131,7 +131,7 @@ struct D2Stage {
     {
 #pragma unroll
         for (int k = 0; k < NV; ++k) {
-            if (!(256 * (k + 1) <= N4 || tid + 256 * k < N4)) break;
+            if (!(NT * (k + 1) <= N4 || tid + NT * k < N4)) break;
             // winner (dy, dx) of every byte -> dy * 16 + dx, four at once
             const uint32_t off = (code[k] & 0x01010101u) | ((code[k] & 0x02020202u) << 3);
             d2[(base[k][0] & 0xffffu) + (off & 0xffu)] = v[k][0];
@@ -146,9 +146,9 @@ struct D2Stage {
         static_assert(COUNT * D2_IMS % 4 == 0, "16-byte stores");
         constexpr int T4 = COUNT * D2_IMS / 4;
 #pragma unroll
-        for (int i = 0; i < (T4 + 255) / 256; ++i)
-            if (256 * (i + 1) <= T4 || tid + 256 * i < T4)
-                reinterpret_cast<floatx4*>(d2)[tid + 256 * i] = floatx4{0.f, 0.f, 0.f, 0.f};
+        for (int i = 0; i < (T4 + NT - 1) / NT; ++i)
+            if (NT * (i + 1) <= T4 || tid + NT * i < T4)
+                reinterpret_cast<floatx4*>(d2)[tid + NT * i] = floatx4{0.f, 0.f, 0.f, 0.f};
     }
 };
 
@@ -242,13 +242,14 @@ __global__ __launch_bounds__(256, 2) void conv2_fwd_kernel(WorkerBuffers wb, int
 //   d W1[c][dy][dx] += d pool1[c][p] * xpad[winner(c,p) + (dy,dx)],   d b1[c] += d pool1[c][p],
 // on the vector ALU, which is idle while the matrix cores run.  A block owns up to DX_IPB images of
 // one worker and walks them DX_G at a time; each wavefront's conv1 sums go to its own partial slot.
-constexpr int DX_G = 2, DX_IPB = 32;
+// DX_G images per group (between two block barriers), DX_NW wavefronts per block
+constexpr int DX_G = 1, DX_NW = 2, DX_NT = 64 * DX_NW, DX_IPB = 32;
 // The conv1 sums leave the registers every DX_FLUSH images, one partial slot per (DX_FLUSH images, wavefront),
 // whatever number of images a block owns (a multiple of DX_FLUSH): the order in which a worker's partial sums
 // are formed and added up then never depends on how the launch was cut into blocks.
 constexpr int DX_FLUSH = 8;
 
-__global__ __launch_bounds__(256, 2) void conv2_dx_kernel(WorkerBuffers wb, int blocks_per_worker, int ipb)
+__global__ __launch_bounds__(DX_NT, 512 / DX_NT) void conv2_dx_kernel(WorkerBuffers wb, int blocks_per_worker, int ipb)
 {
     constexpr int CHS = CHS_DX, D2_IMS = C2 * CHS;
     __shared__ __attribute__((aligned(16))) float tile[DX_G * D2_IMS];  // 69,632 B
@@ -284,23 +285,23 @@ __global__ __launch_bounds__(256, 2) void conv2_dx_kernel(WorkerBuffers wb, int 
 #pragma unroll
     for (int g = 0; g < 8; ++g) wz[g] = W2[((4 * g + q) * C1 + l16) * 9];
 
-    for (int i = tid; i < DX_G * D2_IMS / 4; i += 256)
+    for (int i = tid; i < DX_G * D2_IMS / 4; i += DX_NT)
         reinterpret_cast<float4*>(tile)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int i = tid; i < DX_G * 900; i += 256) xs[i] = 0.f;
-    for (int i = tid; i < DX_G * P1_POS; i += 256) {
+    for (int i = tid; i < DX_G * 900; i += DX_NT) xs[i] = 0.f;
+    for (int i = tid; i < DX_G * P1_POS; i += DX_NT) {
         const int img = i / P1_POS, pos = i % P1_POS;
         a_off[i] = img * D2_IMS + (pos / P1_W) * 16 + pos % P1_W;
         if (img == 0) x_off[pos] = 2 * (pos / P1_W) * 30 + 2 * (pos % P1_W);
     }
     __syncthreads();
 
-    // input pixels of a group: DX_G * 196 float4, at most two per thread
-    constexpr int NX4 = DX_G * (IMG_PIX / 4);
-    float4 xv[2];
+    // input pixels of a group: DX_G * 196 float4
+    constexpr int NX4 = DX_G * (IMG_PIX / 4), NXV = (NX4 + DX_NT - 1) / DX_NT;
+    float4 xv[NXV];
     auto prefetch_x = [&](size_t g0, int valid) {
 #pragma unroll
-        for (int k = 0; k < 2; ++k) {
-            const int i4 = tid + 256 * k;
+        for (int k = 0; k < NXV; ++k) {
+            const int i4 = tid + DX_NT * k;
             xv[k] = (i4 < NX4 && i4 / (IMG_PIX / 4) < valid)
                         ? *reinterpret_cast<const float4*>(wb.x + g0 * IMG_PIX + (size_t)i4 * 4)
                         : make_float4(0.f, 0.f, 0.f, 0.f);
@@ -308,8 +309,8 @@ __global__ __launch_bounds__(256, 2) void conv2_dx_kernel(WorkerBuffers wb, int 
     };
     auto commit_x = [&]() {
 #pragma unroll
-        for (int k = 0; k < 2; ++k) {
-            const int i4 = tid + 256 * k;
+        for (int k = 0; k < NXV; ++k) {
+            const int i4 = tid + DX_NT * k;
             if (i4 >= NX4) break;
             const int img = i4 / (IMG_PIX / 4), r = (i4 % (IMG_PIX / 4)) * 4;  // 28 % 4 == 0: one image row
             float* dst = xs + img * 900 + (r / IMG_W + 1) * 30 + r % IMG_W + 1;
@@ -325,7 +326,7 @@ __global__ __launch_bounds__(256, 2) void conv2_dx_kernel(WorkerBuffers wb, int 
     const float* ax_lane = tile + (tx / 3) * 16 + tx % 3;
     const float* ay_lane = tile + (ty / 3) * 16 + ty % 3;
     const float* az_lane = tile + q * CHS + 2 * 16 + 2;
-    D2Stage<DX_G, CHS> stage;
+    D2Stage<DX_G, CHS, DX_NT> stage;
     stage.init(tid);
     stage.prefetch(wb, (size_t)w * B + s_begin, min(DX_G, s_end - s_begin), tid);
     prefetch_x((size_t)w * B + s_begin, min(DX_G, s_end - s_begin));
@@ -346,7 +347,7 @@ __global__ __launch_bounds__(256, 2) void conv2_dx_kernel(WorkerBuffers wb, int 
         // branch.  The 36 input pixels of conv1's weight gradient are read in front of the matrix work and used
         // behind it; the first A-operand values of the next tile are read during the current one, so that the
         // matrix cores do not wait behind those 36 reads at the start of a tile (LDS reads return in order).
-        static_assert(DX_G == 2, "image of a position is found with one comparison");
+        static_assert(DX_G <= 2, "image of a position is found with one comparison");
         constexpr int N_TILES = (DX_G * P1_POS + 15) / 16, AHEAD = 4;  // A values of channels 0 .. AHEAD-1 read ahead
         const uint8_t* am1_lane = wb.am1 + g0 * P1_SIZE + l16 * P1_POS + 4 * q;
         auto window_bytes = [&](int t) -> uint32_t {
@@ -359,7 +360,7 @@ __global__ __launch_bounds__(256, 2) void conv2_dx_kernel(WorkerBuffers wb, int 
             const int m = 16 * t + l16;  // lane row l16 = position 16t + l16 of the group (rows beyond it read position 0)
             return a_off[m < DX_G * P1_POS ? m : 0];
         };
-        const int t_first = (wave + rot) & 3;
+        const int t_first = (wave + rot) % DX_NW;
         uint32_t win_next = window_bytes(t_first);
         int at = a_base(t_first);
         float ax_next[AHEAD], ay_next[AHEAD];
@@ -368,7 +369,7 @@ __global__ __launch_bounds__(256, 2) void conv2_dx_kernel(WorkerBuffers wb, int 
             ax_next[o] = ax_lane[at + o * CHS];
             ay_next[o] = ay_lane[at + o * CHS];
         }
-        for (int t = t_first; t < N_TILES; t += 4) {
+        for (int t = t_first; t < N_TILES; t += DX_NW) {
             const uint32_t win = win_next;
             // the 3x3 input neighbourhoods at the four winners
             const int mo = min(16 * t + 4 * q, DX_G * P1_POS - 4), img_o = mo >= P1_POS ? 1 : 0, pos_o = mo - img_o * P1_POS;
@@ -379,11 +380,11 @@ __global__ __launch_bounds__(256, 2) void conv2_dx_kernel(WorkerBuffers wb, int 
             float xr[36];
 #pragma unroll
             for (int r = 0; r < 36; ++r) xr[r] = px[r / 9][((r % 9) / 3) * 30 + (r % 9) % 3];
-            win_next = window_bytes(t + 4);
+            win_next = window_bytes(t + DX_NW);
             const float* ax = ax_lane + at;
             const float* ay = ay_lane + at;
             const float* az = az_lane + at;
-            const int at_next = a_base(min(t + 4, N_TILES - 1));
+            const int at_next = a_base(min(t + DX_NW, N_TILES - 1));
             floatx4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int g = 0; g < 8; ++g) {
@@ -425,7 +426,7 @@ __global__ __launch_bounds__(256, 2) void conv2_dx_kernel(WorkerBuffers wb, int 
             gb1 += __shfl_xor(gb1, 16, 64);
             gb1 += __shfl_xor(gb1, 32, 64);
             if (q == 0) {
-                float* part = wb.part1 + ((size_t)w * (4 * ((B + DX_FLUSH - 1) / DX_FLUSH)) + (s0 / DX_FLUSH) * 4 + wave) * OFF_W2;
+                float* part = wb.part1 + ((size_t)w * (DX_NW * ((B + DX_FLUSH - 1) / DX_FLUSH)) + (s0 / DX_FLUSH) * DX_NW + wave) * OFF_W2;
 #pragma unroll
                 for (int i = 0; i < 9; ++i) part[OFF_W1 + l16 * 9 + i] = g1[i];
                 part[OFF_B1 + l16] = gb1;
@@ -529,34 +530,33 @@ __global__ __launch_bounds__(256, 2) void conv2_dw_kernel(WorkerBuffers wb)
 
 }  // namespace
 
-// Images per block: as many as FWD_IPB / DX_IPB when the launch still fills every compute unit twice over
-// (two blocks fit a unit), else fewer (16, 8), so that a small launch does not leave half the chip idle.
-static int images_per_block(int n, int batch, int most)
+// Images per block: as many as FWD_IPB / DX_IPB when the launch still gives every compute unit as many blocks
+// as fit it, else fewer (16, 8), so that a small launch does not leave part of the chip idle.
+static int images_per_block(int n, int batch, int most, int blocks_per_cu)
 {
-    static int slots = 0;
-    if (slots == 0) {
-        int dev = 0, cus = 0;
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
             cus = 256;
-        slots = 2 * cus;
     }
     int ipb = most;
-    while (ipb > DX_FLUSH && n * ((batch + ipb - 1) / ipb) < slots) ipb /= 2;
+    while (ipb > DX_FLUSH && n * ((batch + ipb - 1) / ipb) < blocks_per_cu * cus) ipb /= 2;
     return ipb;
 }
 
 void launch_conv2_fwd(const WorkerBuffers& wb, hipStream_t s)
 {
-    const int ipb = images_per_block(wb.n, wb.B, FWD_IPB), bpw = (wb.B + ipb - 1) / ipb;
+    const int ipb = images_per_block(wb.n, wb.B, FWD_IPB, 2), bpw = (wb.B + ipb - 1) / ipb;
     hipLaunchKernelGGL(conv2_fwd_kernel, dim3(wb.n * bpw), dim3(256), 0, s, wb, bpw, ipb);
 }
 
-int conv1_part_slots(int batch) { return 4 * ((batch + DX_FLUSH - 1) / DX_FLUSH); }
+int conv1_part_slots(int batch) { return DX_NW * ((batch + DX_FLUSH - 1) / DX_FLUSH); }
 
 void launch_conv2_dx(const WorkerBuffers& wb, hipStream_t s)
 {
-    const int ipb = images_per_block(wb.n, wb.B, DX_IPB), bpw = (wb.B + ipb - 1) / ipb;
-    hipLaunchKernelGGL(conv2_dx_kernel, dim3(wb.n * bpw), dim3(256), 0, s, wb, bpw, ipb);
+    const int ipb = images_per_block(wb.n, wb.B, DX_IPB, 512 / DX_NT), bpw = (wb.B + ipb - 1) / ipb;
+    hipLaunchKernelGGL(conv2_dx_kernel, dim3(wb.n * bpw), dim3(DX_NT), 0, s, wb, bpw, ipb);
 }
 
 void launch_conv2_dw(const WorkerBuffers& wb, hipStream_t s)
