@@ -722,6 +722,39 @@ def test_full_size_elastic_average_256_local_copies(ps):
         ps.ps_destroy(ctx)
 
 
+def test_checkpoint_rehydrated_from_host_memory(ps):
+    """A checkpoint that lives outside the device (Section 2.1: the restarted server rehydrates the latest
+    checkpoint from storage): ps_load_snapshot puts it into a ring slot with its version, ps_restore_weights
+    continues from it; workers can read the loaded slot directly."""
+    import torch
+    W, B, lr = 2, 8, 0.05
+    theta0, saved = synth.he_uniform_theta(31), synth.he_uniform_theta(32)
+    ctx = ps.ps_init(ps.make_config(W, B, 2, W, DROP_SEED, P_DROP))
+    try:
+        ps.ps_set_weights(ctx, theta0)
+        mbs = [synth.minibatch_id(w, 0) for w in range(W)]
+        x, y = synth.minibatches(DATA_SEED, mbs, B)
+        xd, yd = _torch_inputs(x, y)
+        e = ps.worker_grads_batched(ctx, range(W), [0, 0], mbs, xd, yd)
+        ps.ps_apply_sync(ctx, e, lr)                                  # version 1
+        ps.ps_load_snapshot(ctx, 1, saved, 41)                        # a checkpoint written at update 41
+        assert np.array_equal(ps.ps_get_weights(ctx, 1), saved) and ps.ps_version(ctx) == 1
+        assert not np.array_equal(ps.ps_get_weights(ctx), saved)      # the server's weights are untouched
+        e = ps.worker_grads_batched(ctx, range(W), [1, 0], mbs, xd, yd)   # worker 0 reads the loaded slot
+        ps.ps_sync(ctx)
+        assert [(m[1], m[2]) for m in ps.ps_queue_meta(ctx)] == [(0, 41), (1, 0)]
+        r = parity.check_worker(ps, ctx, 0, e[0], saved.astype(np.float64), x[0], y[0], mbs[0], DROP_SEED, P_DROP, "loaded slot")
+        assert r["worst"] <= parity.GRAD_TOL
+        assert ps.ps_restore_weights(ctx, 1) == 2                     # both pending gradients are lost
+        assert np.array_equal(ps.ps_get_weights(ctx), saved) and ps.ps_version(ctx) == 41 and ps.ps_queue_meta(ctx) == []
+        for bad_slot in (-1, 2):
+            with pytest.raises(ps.PsError) as err:
+                ps.ps_load_snapshot(ctx, bad_slot, saved, 0)
+            assert err.value.status == ps.PS_EINVAL
+    finally:
+        ps.ps_destroy(ctx)
+
+
 # ------------------------------------------------------------------ edges and errors
 
 def test_edges_and_error_codes(ps):
