@@ -29,17 +29,17 @@ __device__ __forceinline__ floatx4 mfma16(float a, float b, floatx4 c)
 // the matrix cores work on the current one: prefetch_* issues the loads into registers, commit_*
 // writes the registers into the padded LDS planes after the barrier that ends the current group.
 
-// pool1 planes of COUNT images (16 channels, 14x14 interiors); NV float4 per thread.
-template <int COUNT, int CHS>
+// pool1 planes of COUNT images (16 channels, 14x14 interiors); NV float4 per thread of a block of NT.
+template <int COUNT, int CHS, int NT = 256>
 struct Pool1Stage {
     static constexpr int P1_IMS = C1 * CHS;
-    static constexpr int N4 = COUNT * (P1_SIZE / 4), NV = (N4 + 255) / 256;
+    static constexpr int N4 = COUNT * (P1_SIZE / 4), NV = (N4 + NT - 1) / NT;
     floatx4 v[NV];
     uint32_t src[NV];  // float offset of this thread's k-th float4 inside a group of COUNT images
     __device__ __forceinline__ void init(int tid)
     {
 #pragma unroll
-        for (int k = 0; k < NV; ++k) src[k] = (uint32_t)min(tid + 256 * k, N4 - 1) * 4;  // threads without an element repeat the last one
+        for (int k = 0; k < NV; ++k) src[k] = (uint32_t)min(tid + NT * k, N4 - 1) * 4;  // threads without an element repeat the last one
     }
     // images [g0, g0 + valid) exist; the rest of the group repeats the last existing image (its
     // results are never stored), so the loads need no branches
@@ -63,7 +63,7 @@ struct Pool1Stage {
     static __device__ __forceinline__ void build_table(uint16_t* __restrict__ tab, int tid)
     {
         static_assert(COUNT * P1_IMS < (1 << 15), "offsets must fit 15 bits");
-        for (int i4 = tid; i4 < N4; i4 += 256) {
+        for (int i4 = tid; i4 < N4; i4 += NT) {
             const int img = i4 / (P1_SIZE / 4), r = (i4 % (P1_SIZE / 4)) * 4, c = r / P1_POS, pos = r % P1_POS;
             const int base = img * P1_IMS + c * CHS + 17 + (pos / P1_W) * 16 + pos % P1_W;  // interior starts at (1,1)
             tab[i4] = (uint16_t)(base | (pos % P1_W == P1_W - 2 ? 0x8000 : 0));
@@ -73,8 +73,8 @@ struct Pool1Stage {
     {
 #pragma unroll
         for (int k = 0; k < NV; ++k) {
-            const int i4 = tid + 256 * k;
-            if (256 * (k + 1) <= N4 || i4 < N4) {
+            const int i4 = tid + NT * k;
+            if (NT * (k + 1) <= N4 || i4 < N4) {
                 const uint32_t e = tab[i4];
                 float* dst = tile + (e & 0x7fffu);
                 const uint32_t hop = (e >> 15) * 2;  // the next row starts 16 - 14 further on
@@ -156,28 +156,31 @@ struct D2Stage {
 // Forward.  GEMM rows are conv outputs ordered (pooled position, window element) so that the four
 // accumulators of a lane are one 2x2 pool window; columns are the 32 output channels (two 16-wide
 // MFMA tiles sharing the A operand); K = (tap, channel).  A block owns up to FWD_IPB images of one
-// worker and walks them FWD_G at a time (196 pooled positions = 49 row tiles per group).
-constexpr int FWD_G = 4, FWD_IPB = 32;
+// worker and walks them FWD_G at a time (FWD_G * 49 pooled positions, four per row tile), FWD_NW wavefronts
+// per block.
+constexpr int FWD_G = 4, FWD_NW = 4, FWD_NT = 64 * FWD_NW, FWD_IPB = 32;
+constexpr int FWD_TILES = (FWD_G * P2_POS + 3) / 4;
 
-__global__ __launch_bounds__(256, 2) void conv2_fwd_kernel(WorkerBuffers wb, int blocks_per_worker, int ipb)
+__global__ __launch_bounds__(FWD_NT, 512 / FWD_NT) void conv2_fwd_kernel(WorkerBuffers wb, int blocks_per_worker, int ipb)
 {
     constexpr int CHS = CHS_FWD, P1_IMS = C1 * CHS;
-    __shared__ __attribute__((aligned(16))) float tile[FWD_G * P1_IMS];  // 67,584 B
+    __shared__ __attribute__((aligned(16))) float tile[FWD_G * P1_IMS];  // 16,896 B per image
     // pooled position of the group -> offset of its window in the planes / of its output.  On this chip
     // fp32 MFMAs and vector-ALU instructions do not overlap, so index arithmetic inside the tile loop
     // is paid for in matrix time: look it up.
-    __shared__ int win_off[FWD_G * P2_POS], out_off[FWD_G * P2_POS];
-    __shared__ uint16_t stage_tab[Pool1Stage<FWD_G, CHS_FWD>::N4];
+    // (entries past the group's last position, in a last tile that is not full, point at position 0: read, never stored)
+    __shared__ int win_off[4 * FWD_TILES], out_off[4 * FWD_TILES];
+    __shared__ uint16_t stage_tab[Pool1Stage<FWD_G, CHS_FWD, FWD_NT>::N4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, q = lane >> 4, l16 = lane & 15;
     const int w = blockIdx.x / blocks_per_worker, chunk = blockIdx.x % blocks_per_worker;
     const int B = wb.B, s_begin = chunk * ipb, s_end = min(B, s_begin + ipb);
     const float* __restrict__ W2 = worker_theta(wb, w) + OFF_W2;
-    if (tid < FWD_G * P2_POS) {
-        const int img = tid / P2_POS, pos = tid % P2_POS;
-        win_off[tid] = img * P1_IMS + 2 * (pos / P2_W) * 16 + 2 * (pos % P2_W);
-        out_off[tid] = img * P2_SIZE + pos;
+    for (int i = tid; i < 4 * FWD_TILES; i += FWD_NT) {
+        const int e = i < FWD_G * P2_POS ? i : 0, img = e / P2_POS, pos = e % P2_POS;
+        win_off[i] = img * P1_IMS + 2 * (pos / P2_W) * 16 + 2 * (pos % P2_W);
+        out_off[i] = img * P2_SIZE + pos;
     }
-    Pool1Stage<FWD_G, CHS>::build_table(stage_tab, tid);
+    Pool1Stage<FWD_G, CHS, FWD_NT>::build_table(stage_tab, tid);
 
     // B operand of k-step s (channels 4*(s/9) .. +3, tap = s%9): lane (q, l16) holds W2[o][4*(s/9)+q][tap].
     // Taps innermost: the nine A reads of a channel group then share one LDS base address.
@@ -188,13 +191,13 @@ __global__ __launch_bounds__(256, 2) void conv2_fwd_kernel(WorkerBuffers wb, int
         for (int hf = 0; hf < 2; ++hf) wreg[s][hf] = W2[((l16 + 16 * hf) * C1 + 4 * (s / 9) + q) * 9 + s % 9];
     const float bias0 = W2[C2 * C1 * 9 + l16], bias1 = W2[C2 * C1 * 9 + 16 + l16];
 
-    for (int i = tid; i < FWD_G * P1_IMS / 4; i += 256)
+    for (int i = tid; i < FWD_G * P1_IMS / 4; i += FWD_NT)
         reinterpret_cast<float4*>(tile)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
     __syncthreads();
 
     // this lane's part of the A operand address: channel quarter, window element
     const float* a_lane = tile + q * CHS + ((l16 >> 1) & 1) * 16 + (l16 & 1);
-    Pool1Stage<FWD_G, CHS> stage;
+    Pool1Stage<FWD_G, CHS, FWD_NT> stage;
     stage.init(tid);
     stage.prefetch(wb.p1, (size_t)w * B + s_begin, min(FWD_G, s_end - s_begin), tid);
     int rot = 0;
@@ -204,7 +207,7 @@ __global__ __launch_bounds__(256, 2) void conv2_fwd_kernel(WorkerBuffers wb, int
         stage.commit(tile, stage_tab, tid);
         __syncthreads();
         if (s0 + FWD_G < s_end) stage.prefetch(wb.p1, g0 + FWD_G, min(FWD_G, s_end - s0 - FWD_G), tid);
-        for (int t = (wave + rot) & 3; t < FWD_G * P2_POS / 4; t += 4) {
+        for (int t = (wave + rot) % FWD_NW; t < FWD_TILES; t += FWD_NW) {  // which wavefront takes the odd tile rotates
             // A operand: lane row l16 = (pooled position 4t + l16/4, window element l16%4)
             const float* a = a_lane + win_off[4 * t + (l16 >> 2)];
             floatx4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
@@ -547,8 +550,8 @@ static int images_per_block(int n, int batch, int most, int blocks_per_cu)
 
 void launch_conv2_fwd(const WorkerBuffers& wb, hipStream_t s)
 {
-    const int ipb = images_per_block(wb.n, wb.B, FWD_IPB, 2), bpw = (wb.B + ipb - 1) / ipb;
-    hipLaunchKernelGGL(conv2_fwd_kernel, dim3(wb.n * bpw), dim3(256), 0, s, wb, bpw, ipb);
+    const int ipb = images_per_block(wb.n, wb.B, FWD_IPB, 512 / FWD_NT), bpw = (wb.B + ipb - 1) / ipb;
+    hipLaunchKernelGGL(conv2_fwd_kernel, dim3(wb.n * bpw), dim3(FWD_NT), 0, s, wb, bpw, ipb);
 }
 
 int conv1_part_slots(int batch) { return DX_NW * ((batch + DX_FLUSH - 1) / DX_FLUSH); }
